@@ -1,0 +1,144 @@
+/*
+ * tokenbutler.h -- C ABI of the MI355X (gfx950) implementation of TokenButler's decode-time
+ * hot path: score every cached token with a low-dimensional importance query against the
+ * projected key cache, keep a fixed top-k budget per query head (sink prefix and local window
+ * always kept), optionally widen a reused selection with neighbours, and run decode attention
+ * over the selected K/V rows only.
+ *
+ * Conventions shared by every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library never
+ *    allocates, frees or keeps them.  Scratch memory comes in through `ws` (see
+ *    tb_workspace_bytes / tb_workspace_init).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Every call only
+ *    enqueues work on that stream and returns; nothing synchronises.
+ *  - Errors are return codes.  All argument checks happen on the host before anything is
+ *    launched; a failing call launches nothing.
+ *  - K, V, K_imp, W, q, q_imp share one element type (tb_dtype).  Scores, attention output
+ *    and log-sum-exp are always fp32; index lists and counts are int32.
+ *  - Query head h reads KV head h / (Hq / Hkv)  (consecutive query heads share a KV head).
+ *  - Supported shapes: D in {64, 128}; Dimp in {16, 32, 64}; Hq / Hkv in {1, 2, 4, 8};
+ *    N <= 2^20 for selection.  Row starts must be 16-byte aligned: base pointers 16-byte
+ *    aligned and all strides multiples of 8 elements.  Anything else -> TB_ERR_UNSUPPORTED.
+ */
+#ifndef TOKENBUTLER_H_
+#define TOKENBUTLER_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tb_status {
+  TB_OK = 0,
+  TB_ERR_INVALID_ARG = 1, /* null pointer, negative size, inconsistent shape, capacity too small */
+  TB_ERR_UNSUPPORTED = 2, /* well-formed but outside the supported shapes / alignments          */
+  TB_ERR_WORKSPACE = 3,   /* ws is NULL or ws_bytes below tb_workspace_bytes()                  */
+  TB_ERR_HIP = 4          /* a HIP launch reported an error                                     */
+} tb_status;
+
+typedef enum tb_dtype { TB_F32 = 0, TB_BF16 = 1 } tb_dtype;
+
+/* One layer's cache view.  Plain data, read during the call only.
+ * K, V   : [B][Hkv][>=N][D]     element (b,h,n,d) at  b*stride_b + h*stride_h + n*stride_n + d
+ * K_imp  : [B][Hkv][>=N][Dimp]  same addressing with the ki_ strides
+ * Strides are in elements; the innermost dimension is contiguous. */
+typedef struct tb_cache_desc {
+  int32_t B, Hq, Hkv, D, Dimp;
+  int32_t dtype; /* tb_dtype */
+  int64_t N;     /* tokens currently valid in the cache */
+  int64_t k_stride_b, k_stride_h, k_stride_n;
+  int64_t v_stride_b, v_stride_h, v_stride_n;
+  int64_t ki_stride_b, ki_stride_h, ki_stride_n;
+} tb_cache_desc;
+
+/* Operation selector for tb_workspace_bytes. */
+enum { TB_OP_SELECT = 1, TB_OP_ATTN = 2, TB_OP_DECODE_STEP = 3 };
+
+/* Key-cache projection (Sec. 3.1, "Key-cache projection": K_imp = K W_K, W_K in R^{D x Dimp}).
+ * Fills K_imp[b,h,n,:] = round(K[b,h,n,:] . W[hw]) for n_begin <= n < n_end, fp32 accumulation,
+ * one round-to-nearest-even to the storage type.  Covers both the one-row append and the
+ * batched deferred projection of a whole window of rows (Sec. 3.3).
+ * W: [Hw][D][Dimp] contiguous; Hw == 1 (one matrix per layer, as the paper writes it) or
+ * Hw == Hkv.  Requires 0 <= n_begin <= n_end <= desc->N.  Empty range: no-op, TB_OK. */
+tb_status tb_project_keys(const tb_cache_desc* desc, const void* K, const void* W, int32_t Hw, void* Kimp,
+                          int64_t n_begin, int64_t n_end, void* stream);
+
+/* Importance scoring (abstract; Sec. 3.4 "score computation against all projected keys").
+ * scores[b,h,n] = scale * sum_j q_imp[b,h,j] * K_imp[b,h/g,n,j]   for 0 <= n < desc->N.
+ * q_imp: [B][Hq][Dimp] contiguous.  scores: fp32 [B][Hq][score_stride], score_stride >= N and
+ * a multiple of 4.  The paper gives no normalisation of the score; `scale` is explicit. */
+tb_status tb_score(const tb_cache_desc* desc, const void* q_imp, const void* Kimp, float scale, float* scores,
+                   int64_t score_stride, void* stream);
+
+/* Token selection policy (Sec. 4 "Token Selection Policy").  Per (b,h): candidates are the
+ * positions [lo, hi) with lo = min(sink, N), hi = max(lo, N - window); the kk = min(k, hi-lo)
+ * candidates with the largest score are kept.  Ordering: larger score first, NaN counts as
+ * -inf, -0 equals +0, equal scores -> lower index first.  Output per (b,h), ascending:
+ *   idx = [0,lo) ++ ascending(kept) ++ [hi,N),   count = lo + kk + (N - hi).
+ * idx: int32 [B][Hq][idx_cap], idx_cap >= lo + kk + (N - hi); entries beyond count are left
+ * untouched.  count: int32 [B][Hq].  ws: see tb_workspace_bytes(TB_OP_SELECT, ...). */
+tb_status tb_select_topk(const tb_cache_desc* desc, const float* scores, int64_t score_stride, int32_t k,
+                         int32_t sink, int32_t window, int32_t* idx, int32_t* count, int64_t idx_cap, void* ws,
+                         size_t ws_bytes, void* stream);
+
+/* Neighbour fetching (Sec. 3.4 "Neighbor fetching").  idx_in lists must be strictly ascending
+ * and within [0, N).
+ * mode 0: idx_out = ascending, duplicate-free union over the input of [i-radius, i+radius]
+ *         clipped to [0, N).  cap_out >= min(N, (2*radius+1) * cap_in) is required.
+ * mode 1: cluster-aware fetch: consecutive selected positions form clusters and every
+ *         selected token adds the next free position past its cluster (left-to-right; free
+ *         positions taken by an earlier cluster are skipped), 2*count positions unless the
+ *         sweep reaches N.  radius is ignored.  cap_out >= min(N, 2 * cap_in).
+ * Units are the B*Hq lists; count_out[u] receives the output length. */
+tb_status tb_expand_neighbors(int32_t B, int32_t Hq, int64_t N, int32_t radius, int32_t mode,
+                              const int32_t* idx_in, const int32_t* count_in, int64_t cap_in, int32_t* idx_out,
+                              int32_t* count_out, int64_t cap_out, void* stream);
+
+/* Decode attention over the selected rows (Sec. 3.3: attention touches sink, window and
+ * important tokens only; with every token selected it is dense decode attention).
+ *   out[b,h,:] = sum_i softmax_i(sm_scale * q[b,h] . K[b,h/g,n_i]) * V[b,h/g,n_i]
+ * where n_i runs over idx[b,h,0:count[b,h]] followed by the dense range [tail_begin, tail_end)
+ * (tokens appended since the list was made, which are always attended while a selection is
+ * reused across a prediction interval; pass tail_begin == tail_end for none).
+ * q: [B][Hq][D] contiguous.  idx entries must lie in [0, desc->N); tail_end <= desc->N.
+ * max_count: host-side upper bound on count[b,h] (<= idx_cap) used to size the launch; a list
+ * longer than max_count is truncated to it.  out: fp32 [B][Hq][D]; lse: fp32 [B][Hq] or NULL.
+ * An empty list gives out = 0 and lse = -inf.  ws: tb_workspace_bytes(TB_OP_ATTN, ...). */
+tb_status tb_sparse_decode_attn(const tb_cache_desc* desc, const void* q, const void* K, const void* V,
+                                const int32_t* idx, const int32_t* count, int64_t idx_cap, int64_t max_count,
+                                int64_t tail_begin, int64_t tail_end, float sm_scale, float* out, float* lse,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/* One prediction step in a single enqueue: tb_score -> tb_select_topk -> tb_sparse_decode_attn
+ * with the first selection pass folded into the scoring kernel.  Results (scores, idx, count,
+ * out, lse) are identical to calling the three entry points one after the other.
+ * ws: tb_workspace_bytes(TB_OP_DECODE_STEP, ...). */
+tb_status tb_decode_step(const tb_cache_desc* desc, const void* q_imp, const void* Kimp, float score_scale,
+                         const void* q, const void* K, const void* V, int32_t k, int32_t sink, int32_t window,
+                         float sm_scale, float* scores, int64_t score_stride, int32_t* idx, int32_t* count,
+                         int64_t idx_cap, float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* Scratch size in bytes for `op` on this cache shape.  max_count is the longest list the
+ * attention will see, tail included (ignored for TB_OP_SELECT; for TB_OP_DECODE_STEP it is
+ * the list length the selection policy produces, lo + kk + N - hi).  Returns 0 on invalid
+ * input.  A workspace of the TB_OP_DECODE_STEP size serves all three operations on that
+ * shape.  The workspace pointer must be 16-byte aligned. */
+size_t tb_workspace_bytes(int32_t op, const tb_cache_desc* desc, int64_t max_count);
+
+/* A workspace must be zero-filled once before its first use (this call enqueues that fill;
+ * any other device memset does as well).  Every entry point leaves the workspace ready for the
+ * next call, provided the calls that share it run one after the other on one stream and use
+ * the same B and Hq.  Calls that overlap in time need separate workspaces. */
+tb_status tb_workspace_init(void* ws, size_t ws_bytes, void* stream);
+
+const char* tb_status_string(tb_status s);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int32_t tb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOKENBUTLER_H_ */

@@ -1,0 +1,282 @@
+// C ABI of libtokenbutler: argument validation on the host, workspace layout, launch plans.
+// Every entry point only enqueues kernels on the caller's stream.
+#include "tb_internal.h"
+
+namespace tb {
+
+AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
+  // Aim for a few workgroups per compute unit (256 CUs) so that the gathers of the whole
+  // chip are in flight together; a workgroup takes whole wave tiles.
+  AttnPlan p;
+  if (max_rows <= 0 || units <= 0) {
+    p.rows_per_wg = tile_rows_per_wg;
+    p.nsplit = 1;
+    return p;
+  }
+  const int64_t target_wgs = 1024;
+  int64_t want = (target_wgs + units - 1) / units;
+  const int64_t max_split = (max_rows + tile_rows_per_wg - 1) / tile_rows_per_wg;
+  if (want > max_split) want = max_split;
+  if (want < 1) want = 1;
+  int64_t rows = (max_rows + want - 1) / want;
+  rows = (rows + tile_rows_per_wg - 1) / tile_rows_per_wg * tile_rows_per_wg;
+  p.rows_per_wg = static_cast<int>(rows);
+  p.nsplit = static_cast<int>((max_rows + rows - 1) / rows);
+  return p;
+}
+
+WsLayout ws_layout(int64_t units, int D, int nsplit) {
+  WsLayout w;
+  w.hist_off = align_up(static_cast<size_t>(units) * sizeof(uint32_t), 256);
+  w.part_off = w.hist_off + align_up(static_cast<size_t>(units) * kHistBinsHost * sizeof(uint32_t), 256);
+  w.total = w.part_off + align_up(static_cast<size_t>(units) * nsplit * (D + 2) * sizeof(float), 256);
+  return w;
+}
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+tb_status check_desc(const tb_cache_desc* d) {
+  if (!d) return TB_ERR_INVALID_ARG;
+  if (d->B < 0 || d->Hq < 0 || d->Hkv < 0 || d->N < 0) return TB_ERR_INVALID_ARG;
+  if (d->dtype != TB_F32 && d->dtype != TB_BF16) return TB_ERR_INVALID_ARG;
+  if (d->Hkv == 0 ? d->Hq != 0 : (d->Hq % d->Hkv) != 0) return TB_ERR_INVALID_ARG;
+  if (d->D != 64 && d->D != 128) return TB_ERR_UNSUPPORTED;
+  if (d->Dimp != 16 && d->Dimp != 32 && d->Dimp != 64) return TB_ERR_UNSUPPORTED;
+  if (d->Hkv > 0) {
+    const int g = d->Hq / d->Hkv;
+    if (g != 1 && g != 2 && g != 4 && g != 8) return TB_ERR_UNSUPPORTED;
+  }
+  if (d->B > 65535 || d->Hq > 65535) return TB_ERR_UNSUPPORTED;
+  return TB_OK;
+}
+
+tb_status check_strides(const tb_cache_desc* d, int64_t sb, int64_t sh, int64_t sn, int inner) {
+  if (sb < 0 || sh < 0 || sn < inner) return TB_ERR_INVALID_ARG;
+  if ((sb | sh | sn) % 8) return TB_ERR_UNSUPPORTED;
+  (void)d;
+  return TB_OK;
+}
+
+#define TB_TRY(expr)                 \
+  do {                               \
+    const tb_status _s = (expr);     \
+    if (_s != TB_OK) return _s;      \
+  } while (0)
+
+struct Policy {
+  int64_t lo, hi, kk, count;
+};
+Policy policy(int64_t N, int32_t k, int32_t sink, int32_t window) {
+  Policy p;
+  p.lo = sink < N ? sink : N;
+  p.hi = (N - window > p.lo) ? (N - window) : p.lo;
+  const int64_t nc = p.hi - p.lo;
+  p.kk = k < nc ? k : nc;
+  p.count = p.lo + p.kk + (N - p.hi);
+  return p;
+}
+
+tb_status check_score_args(const tb_cache_desc* d, const void* q_imp, const void* Kimp, const float* scores,
+                           int64_t score_stride) {
+  TB_TRY(check_desc(d));
+  if (!q_imp || !Kimp || !scores) return TB_ERR_INVALID_ARG;
+  if (score_stride < d->N) return TB_ERR_INVALID_ARG;
+  if (score_stride % 4) return TB_ERR_UNSUPPORTED;
+  TB_TRY(check_strides(d, d->ki_stride_b, d->ki_stride_h, d->ki_stride_n, d->Dimp));
+  if (!aligned16(q_imp) || !aligned16(Kimp) || !aligned16(scores)) return TB_ERR_UNSUPPORTED;
+  return TB_OK;
+}
+
+tb_status check_select_args(const tb_cache_desc* d, const float* scores, int64_t score_stride, int32_t k,
+                            int32_t sink, int32_t window, const int32_t* idx, const int32_t* count,
+                            int64_t idx_cap) {
+  TB_TRY(check_desc(d));
+  if (!scores || !idx || !count) return TB_ERR_INVALID_ARG;
+  if (k < 0 || sink < 0 || window < 0) return TB_ERR_INVALID_ARG;
+  if (score_stride < d->N) return TB_ERR_INVALID_ARG;
+  if (score_stride % 4 || !aligned16(scores)) return TB_ERR_UNSUPPORTED;
+  if (d->N > kSelectMaxN) return TB_ERR_UNSUPPORTED;
+  const Policy p = policy(d->N, k, sink, window);
+  if (idx_cap < p.count) return TB_ERR_INVALID_ARG;
+  return TB_OK;
+}
+
+tb_status check_attn_args(const tb_cache_desc* d, const void* q, const void* K, const void* V, const int32_t* idx,
+                          const int32_t* count, int64_t idx_cap, int64_t max_count, int64_t tail_begin,
+                          int64_t tail_end, const float* out) {
+  TB_TRY(check_desc(d));
+  if (!q || !K || !V || !idx || !count || !out) return TB_ERR_INVALID_ARG;
+  if (idx_cap < 0 || max_count < 0 || max_count > idx_cap) return TB_ERR_INVALID_ARG;
+  if (tail_begin < 0 || tail_begin > tail_end || tail_end > d->N) return TB_ERR_INVALID_ARG;
+  if (d->N == 0 && max_count > 0) return TB_ERR_INVALID_ARG;
+  TB_TRY(check_strides(d, d->k_stride_b, d->k_stride_h, d->k_stride_n, d->D));
+  TB_TRY(check_strides(d, d->v_stride_b, d->v_stride_h, d->v_stride_n, d->D));
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return TB_ERR_UNSUPPORTED;
+  if (max_count + (tail_end - tail_begin) > (int64_t{1} << 30)) return TB_ERR_UNSUPPORTED;
+  return TB_OK;
+}
+
+}  // namespace
+}  // namespace tb
+
+using namespace tb;
+
+extern "C" {
+
+tb_status tb_project_keys(const tb_cache_desc* d, const void* K, const void* W, int32_t Hw, void* Kimp,
+                          int64_t n_begin, int64_t n_end, void* stream) {
+  TB_TRY(check_desc(d));
+  if (!K || !W || !Kimp) return TB_ERR_INVALID_ARG;
+  if (Hw != 1 && Hw != d->Hkv) return TB_ERR_INVALID_ARG;
+  if (n_begin < 0 || n_begin > n_end || n_end > d->N) return TB_ERR_INVALID_ARG;
+  TB_TRY(check_strides(d, d->k_stride_b, d->k_stride_h, d->k_stride_n, d->D));
+  TB_TRY(check_strides(d, d->ki_stride_b, d->ki_stride_h, d->ki_stride_n, d->Dimp));
+  if (!aligned16(K) || !aligned16(W) || !aligned16(Kimp)) return TB_ERR_UNSUPPORTED;
+  return launch_project(d, K, W, Hw, Kimp, n_begin, n_end, static_cast<hipStream_t>(stream));
+}
+
+tb_status tb_score(const tb_cache_desc* d, const void* q_imp, const void* Kimp, float scale, float* scores,
+                   int64_t score_stride, void* stream) {
+  TB_TRY(check_score_args(d, q_imp, Kimp, scores, score_stride));
+  if (d->B == 0 || d->Hq == 0) return TB_OK;
+  ScoreLaunch L{d, q_imp, Kimp, scale, scores, score_stride, nullptr, 0, 0};
+  return launch_score(L, static_cast<hipStream_t>(stream));
+}
+
+tb_status tb_select_topk(const tb_cache_desc* d, const float* scores, int64_t score_stride, int32_t k, int32_t sink,
+                         int32_t window, int32_t* idx, int32_t* count, int64_t idx_cap, void* ws, size_t ws_bytes,
+                         void* stream) {
+  TB_TRY(check_select_args(d, scores, score_stride, k, sink, window, idx, count, idx_cap));
+  const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
+  if (units == 0) return TB_OK;
+  const WsLayout w = ws_layout(units, d->D, 0);
+  if (!ws || !aligned16(ws) || ws_bytes < w.part_off) return TB_ERR_WORKSPACE;
+  const Policy p = policy(d->N, k, sink, window);
+  SelectLaunch L;
+  L.units = units;
+  L.N = d->N;
+  L.scores = scores;
+  L.score_stride = score_stride;
+  L.kk = static_cast<int32_t>(p.kk);
+  L.lo = static_cast<int32_t>(p.lo);
+  L.hi = static_cast<int32_t>(p.hi);
+  L.idx = idx;
+  L.count = count;
+  L.idx_cap = idx_cap;
+  L.hist = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + w.hist_off);
+  L.hist_ready = false;
+  return launch_select(L, static_cast<hipStream_t>(stream));
+}
+
+tb_status tb_expand_neighbors(int32_t B, int32_t Hq, int64_t N, int32_t radius, int32_t mode, const int32_t* idx_in,
+                              const int32_t* count_in, int64_t cap_in, int32_t* idx_out, int32_t* count_out,
+                              int64_t cap_out, void* stream) {
+  if (B < 0 || Hq < 0 || N < 0 || radius < 0 || cap_in < 0 || cap_out < 0) return TB_ERR_INVALID_ARG;
+  if (mode != 0 && mode != 1) return TB_ERR_INVALID_ARG;
+  if (!idx_in || !count_in || !idx_out || !count_out) return TB_ERR_INVALID_ARG;
+  if (idx_in == idx_out) return TB_ERR_INVALID_ARG;
+  if (B > 65535 || Hq > 65535 || N > (int64_t{1} << 30) || radius > (1 << 20)) return TB_ERR_UNSUPPORTED;
+  const int64_t mult = (mode == 0) ? (2 * static_cast<int64_t>(radius) + 1) : 2;
+  int64_t need = mult * cap_in;
+  if (need > N) need = N;
+  if (cap_out < need) return TB_ERR_INVALID_ARG;
+  return launch_expand(static_cast<int64_t>(B) * Hq, N, radius, mode, idx_in, count_in, cap_in, idx_out, count_out,
+                       cap_out, static_cast<hipStream_t>(stream));
+}
+
+tb_status tb_sparse_decode_attn(const tb_cache_desc* d, const void* q, const void* K, const void* V,
+                                const int32_t* idx, const int32_t* count, int64_t idx_cap, int64_t max_count,
+                                int64_t tail_begin, int64_t tail_end, float sm_scale, float* out, float* lse,
+                                void* ws, size_t ws_bytes, void* stream) {
+  TB_TRY(check_attn_args(d, q, K, V, idx, count, idx_cap, max_count, tail_begin, tail_end, out));
+  const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
+  if (units == 0) return TB_OK;
+  const int64_t rows = max_count + (tail_end - tail_begin);
+  const AttnPlan plan = attn_plan(units, rows, attn_tile_rows_per_wg(d->dtype, d->D));
+  const WsLayout w = ws_layout(units, d->D, plan.nsplit);
+  if (!ws || !aligned16(ws) || ws_bytes < w.total) return TB_ERR_WORKSPACE;
+  AttnLaunch L{d,   q,   K,   V,
+               idx, count, idx_cap, max_count, tail_begin, tail_end,
+               sm_scale, out, lse,
+               reinterpret_cast<float*>(static_cast<char*>(ws) + w.part_off),
+               reinterpret_cast<uint32_t*>(ws), plan};
+  return launch_attn(L, static_cast<hipStream_t>(stream));
+}
+
+tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* Kimp, float score_scale,
+                         const void* q, const void* K, const void* V, int32_t k, int32_t sink, int32_t window,
+                         float sm_scale, float* scores, int64_t score_stride, int32_t* idx, int32_t* count,
+                         int64_t idx_cap, float* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  TB_TRY(check_score_args(d, q_imp, Kimp, scores, score_stride));
+  TB_TRY(check_select_args(d, scores, score_stride, k, sink, window, idx, count, idx_cap));
+  const Policy p = policy(d->N, k, sink, window);
+  TB_TRY(check_attn_args(d, q, K, V, idx, count, idx_cap, p.count, 0, 0, out));
+  const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
+  if (units == 0) return TB_OK;
+  const AttnPlan plan = attn_plan(units, p.count, attn_tile_rows_per_wg(d->dtype, d->D));
+  const WsLayout w = ws_layout(units, d->D, plan.nsplit);
+  if (!ws || !aligned16(ws) || ws_bytes < w.total) return TB_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint32_t* hist = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + w.hist_off);
+  const bool need_hist = p.kk > 0 && p.kk < p.hi - p.lo;
+
+  ScoreLaunch S{d, q_imp, Kimp, score_scale, scores, score_stride, need_hist ? hist : nullptr,
+                static_cast<int32_t>(p.lo), static_cast<int32_t>(p.hi)};
+  TB_TRY(launch_score(S, st));
+
+  SelectLaunch L;
+  L.units = units;
+  L.N = d->N;
+  L.scores = scores;
+  L.score_stride = score_stride;
+  L.kk = static_cast<int32_t>(p.kk);
+  L.lo = static_cast<int32_t>(p.lo);
+  L.hi = static_cast<int32_t>(p.hi);
+  L.idx = idx;
+  L.count = count;
+  L.idx_cap = idx_cap;
+  L.hist = hist;
+  L.hist_ready = true;
+  TB_TRY(launch_select(L, st));
+
+  AttnLaunch A{d,   q,   K,   V,
+               idx, count, idx_cap, p.count, 0, 0,
+               sm_scale, out, lse,
+               reinterpret_cast<float*>(static_cast<char*>(ws) + w.part_off),
+               reinterpret_cast<uint32_t*>(ws), plan};
+  return launch_attn(A, st);
+}
+
+size_t tb_workspace_bytes(int32_t op, const tb_cache_desc* d, int64_t max_count) {
+  if (check_desc(d) != TB_OK || max_count < 0) return 0;
+  const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
+  if (op == TB_OP_SELECT) return ws_layout(units, d->D, 0).part_off;
+  if (op == TB_OP_ATTN || op == TB_OP_DECODE_STEP) {
+    const AttnPlan plan = attn_plan(units, max_count, attn_tile_rows_per_wg(d->dtype, d->D));
+    return ws_layout(units, d->D, plan.nsplit).total;
+  }
+  return 0;
+}
+
+tb_status tb_workspace_init(void* ws, size_t ws_bytes, void* stream) {
+  if (!ws && ws_bytes) return TB_ERR_INVALID_ARG;
+  if (ws_bytes % 4 || (reinterpret_cast<uintptr_t>(ws) & 3u)) return TB_ERR_INVALID_ARG;
+  return launch_fill_zero(ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+const char* tb_status_string(tb_status s) {
+  switch (s) {
+    case TB_OK: return "ok";
+    case TB_ERR_INVALID_ARG: return "invalid argument";
+    case TB_ERR_UNSUPPORTED: return "unsupported shape, dtype or alignment";
+    case TB_ERR_WORKSPACE: return "workspace missing or too small";
+    case TB_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int32_t tb_version(void) { return 100; }
+
+}  // extern "C"

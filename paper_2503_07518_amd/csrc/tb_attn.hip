@@ -1,0 +1,278 @@
+// Decode attention over a per-head list of selected rows (gather fused into the kernel: no
+// intermediate "important buffer" copy is made).
+//
+// Work split: grid (nsplit, Hq, B).  A workgroup of 4 waves takes a contiguous slice of the
+// head's list; each wave walks its part in tiles of 8*GPW rows, where GPW = 64/LPR row groups
+// and LPR = D*sizeof(T)/16 lanes cover one row with a 128-bit load each (bf16, D=128: 16
+// lanes per 256 B row, 4 rows per wave instruction, 32-row tiles).  All K and V loads of a
+// tile are issued before the first one is consumed, so a wave keeps 16 KiB of gathers in
+// flight.  Every lane group runs its own online softmax (running max, running sum, fp32
+// accumulator slice of D/LPR elements) in the base-2 domain; groups are merged by wave
+// shuffles, waves through LDS, and workgroups through fp32 partials in the workspace: the
+// last workgroup of a head to arrive (device-scope counter) combines the partials in split
+// order, so the result does not depend on arrival order.
+#include "tb_device.h"
+#include "tb_internal.h"
+
+namespace tb {
+namespace {
+
+constexpr int kAttnThreads = 256;
+constexpr int kAttnWaves = kAttnThreads / kWave;
+constexpr int kLoadsPerTile = 8;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct AttnArgs {
+  const void* q;
+  const void* K;
+  const void* V;
+  const int32_t* idx;
+  const int32_t* count;
+  int64_t idx_cap, max_count, tail_begin, tail_end, N;
+  int64_t k_stride_b, k_stride_h, k_stride_n;
+  int64_t v_stride_b, v_stride_h, v_stride_n;
+  float sm_scale_log2;
+  float* out;
+  float* lse;
+  float* partials;
+  uint32_t* counters;
+  int32_t Hq, g, rows_per_wg, nsplit;
+};
+
+__device__ inline float exp2_safe(float d) { return __builtin_amdgcn_exp2f(d); }
+
+template <typename T, int D>
+__global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
+  constexpr int EPL = Pack16<T>::kElts;    // elements per lane
+  constexpr int LPR = D / EPL;             // lanes per row
+  constexpr int GPW = kWave / LPR;         // row groups per wave
+  constexpr int TILE = kLoadsPerTile * GPW;  // rows per wave tile
+  static_assert(LPR >= 4 && LPR <= 32, "row must span 4..32 lanes");
+
+  __shared__ float s_m[kAttnWaves], s_l[kAttnWaves];
+  __shared__ float s_acc[kAttnWaves][D];
+  __shared__ uint32_t s_last;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  const int wave = tid / kWave;
+  const int grp = lane / LPR;
+  const int sub = lane % LPR;
+  const int split = blockIdx.x;
+  const int h = blockIdx.y;
+  const int b = blockIdx.z;
+  const int64_t u = static_cast<int64_t>(b) * a.Hq + h;
+  const int hkv = h / a.g;
+
+  int64_t cnt = a.count[u];
+  cnt = cnt < 0 ? 0 : (cnt > a.max_count ? a.max_count : cnt);
+  const int64_t total = cnt + (a.tail_end - a.tail_begin);
+
+  const int64_t wg_beg = static_cast<int64_t>(split) * a.rows_per_wg;
+  const int rows_per_wave = a.rows_per_wg / kAttnWaves;
+  int64_t w_beg = wg_beg + static_cast<int64_t>(wave) * rows_per_wave;
+  int64_t w_end = w_beg + rows_per_wave;
+  if (w_end > total) w_end = total;
+
+  const T* kbase = static_cast<const T*>(a.K) + b * a.k_stride_b + hkv * a.k_stride_h + sub * EPL;
+  const T* vbase = static_cast<const T*>(a.V) + b * a.v_stride_b + hkv * a.v_stride_h + sub * EPL;
+  const int32_t* list = a.idx + u * a.idx_cap;
+
+  float qv[EPL];
+  Pack16<T>::load(static_cast<const T*>(a.q) + u * D + sub * EPL, qv);
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) qv[e] *= a.sm_scale_log2;
+
+  float m = -INFINITY, l = 0.f;
+  float acc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+
+  for (int64_t t0 = w_beg; t0 < w_end; t0 += TILE) {
+    // lanes 0..TILE-1 fetch the row numbers of this tile (selected list, then the dense tail)
+    int32_t n_mine = -1;
+    {
+      const int64_t i = t0 + lane;
+      if (lane < TILE && i < w_end) {
+        int64_t n = (i < cnt) ? static_cast<int64_t>(list[i]) : a.tail_begin + (i - cnt);
+        n = n < 0 ? 0 : (n >= a.N ? a.N - 1 : n);  // keep the gather inside the cache whatever the list holds
+        n_mine = static_cast<int32_t>(n);
+      }
+    }
+    float kv[kLoadsPerTile][EPL], vv[kLoadsPerTile][EPL];
+    bool valid[kLoadsPerTile];
+#pragma unroll
+    for (int t = 0; t < kLoadsPerTile; ++t) {
+      const int32_t n = __shfl(n_mine, t * GPW + grp, kWave);
+      valid[t] = n >= 0;
+      const int64_t row = valid[t] ? n : 0;
+      Pack16<T>::load(kbase + row * a.k_stride_n, kv[t]);
+      Pack16<T>::load(vbase + row * a.v_stride_n, vv[t]);
+    }
+    float sc[kLoadsPerTile];
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < kLoadsPerTile; ++t) {
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kv[t][e], s);
+#pragma unroll
+      for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off, kWave);
+      sc[t] = valid[t] ? s : -INFINITY;
+      tmax = fmaxf(tmax, sc[t]);
+    }
+    const float m_new = fmaxf(m, tmax);
+    if (m_new > -INFINITY) {
+      const float alpha = exp2_safe(m - m_new);  // m = -inf -> 0
+      l *= alpha;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] *= alpha;
+#pragma unroll
+      for (int t = 0; t < kLoadsPerTile; ++t) {
+        const float p = exp2_safe(sc[t] - m_new);  // invalid -> 0
+        l += p;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vv[t][e], acc[e]);
+      }
+      m = m_new;
+    }
+  }
+
+  // merge the row groups of the wave
+#pragma unroll
+  for (int off = LPR; off < kWave; off <<= 1) {
+    const float m_o = __shfl_xor(m, off, kWave);
+    const float l_o = __shfl_xor(l, off, kWave);
+    const float m_n = fmaxf(m, m_o);
+    const float wa = (m_n > -INFINITY) ? exp2_safe(m - m_n) : 0.f;
+    const float wb = (m_n > -INFINITY) ? exp2_safe(m_o - m_n) : 0.f;
+    l = l * wa + l_o * wb;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const float a_o = __shfl_xor(acc[e], off, kWave);
+      acc[e] = acc[e] * wa + a_o * wb;
+    }
+    m = m_n;
+  }
+  if (grp == 0) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) s_acc[wave][sub * EPL + e] = acc[e];
+    if (sub == 0) {
+      s_m[wave] = m;
+      s_l[wave] = l;
+    }
+  }
+  __syncthreads();
+
+  // merge the waves of the workgroup: thread d < D owns output element d
+  float M = -INFINITY, L = 0.f, o = 0.f;
+  if (tid < D) {
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) M = fmaxf(M, s_m[w]);
+    if (M > -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < kAttnWaves; ++w) {
+        const float wgt = exp2_safe(s_m[w] - M);
+        L += s_l[w] * wgt;
+        o += s_acc[w][tid] * wgt;
+      }
+    }
+  }
+
+  if (a.nsplit == 1) {
+    if (tid < D) a.out[u * D + tid] = (L > 0.f) ? o / L : 0.f;
+    if (tid == 0 && a.lse) a.lse[u] = (L > 0.f) ? M * kLn2 + __logf(L) : -INFINITY;
+    return;
+  }
+
+  // several workgroups per head: publish the partial, the last one to arrive combines
+  float* part = a.partials + (u * a.nsplit + split) * (D + 2);
+  if (tid < D) part[tid] = o;
+  if (tid == 0) {
+    part[D] = M;
+    part[D + 1] = L;
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t ticket = __hip_atomic_fetch_add(&a.counters[u], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (ticket == static_cast<uint32_t>(a.nsplit - 1)) ? 1u : 0u;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  if (tid < D) {
+    const float* p0 = a.partials + u * a.nsplit * (D + 2);
+    float Mg = -INFINITY;
+    for (int s = 0; s < a.nsplit; ++s) Mg = fmaxf(Mg, p0[s * (D + 2) + D]);
+    float Lg = 0.f, og = 0.f;
+    if (Mg > -INFINITY) {
+      for (int s = 0; s < a.nsplit; ++s) {
+        const float wgt = exp2_safe(p0[s * (D + 2) + D] - Mg);
+        Lg += p0[s * (D + 2) + D + 1] * wgt;
+        og += p0[s * (D + 2) + tid] * wgt;
+      }
+    }
+    a.out[u * D + tid] = (Lg > 0.f) ? og / Lg : 0.f;
+    if (tid == 0 && a.lse) a.lse[u] = (Lg > 0.f) ? Mg * kLn2 + __logf(Lg) : -INFINITY;
+  }
+  if (tid == 0) __hip_atomic_store(&a.counters[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <typename T, int D>
+tb_status launch_td(const AttnLaunch& L, hipStream_t st) {
+  const tb_cache_desc& d = *L.desc;
+  AttnArgs a;
+  a.q = L.q;
+  a.K = L.K;
+  a.V = L.V;
+  a.idx = L.idx;
+  a.count = L.count;
+  a.idx_cap = L.idx_cap;
+  a.max_count = L.max_count;
+  a.tail_begin = L.tail_begin;
+  a.tail_end = L.tail_end;
+  a.N = d.N;
+  a.k_stride_b = d.k_stride_b;
+  a.k_stride_h = d.k_stride_h;
+  a.k_stride_n = d.k_stride_n;
+  a.v_stride_b = d.v_stride_b;
+  a.v_stride_h = d.v_stride_h;
+  a.v_stride_n = d.v_stride_n;
+  a.sm_scale_log2 = L.sm_scale * kLog2e;
+  a.out = L.out;
+  a.lse = L.lse;
+  a.partials = L.partials;
+  a.counters = L.counters;
+  a.Hq = d.Hq;
+  a.g = d.Hq / d.Hkv;
+  a.rows_per_wg = L.plan.rows_per_wg;
+  a.nsplit = L.plan.nsplit;
+  dim3 grid(L.plan.nsplit, d.Hq, d.B);
+  hipLaunchKernelGGL((attn_kernel<T, D>), grid, dim3(kAttnThreads), 0, st, a);
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+int attn_tile_rows_per_wg(int dtype, int D) {
+  const int elt = dtype == TB_F32 ? 4 : 2;
+  const int lpr = D * elt / 16;
+  return kAttnWaves * kLoadsPerTile * (kWave / lpr);
+}
+
+tb_status launch_attn(const AttnLaunch& L, hipStream_t st) {
+  const tb_cache_desc& d = *L.desc;
+  if (d.B == 0 || d.Hq == 0) return TB_OK;
+  if (d.dtype == TB_F32) {
+    if (d.D == 64) return launch_td<float, 64>(L, st);
+    if (d.D == 128) return launch_td<float, 128>(L, st);
+  } else {
+    if (d.D == 64) return launch_td<bf16_t, 64>(L, st);
+    if (d.D == 128) return launch_td<bf16_t, 128>(L, st);
+  }
+  return TB_ERR_UNSUPPORTED;
+}
+
+}  // namespace tb

@@ -1,0 +1,126 @@
+// Device-side helpers shared by the HIP kernels of the TokenButler decode hot path (gfx950,
+// wave64).  Nothing here is used by, or shared with, the CPU oracle.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tb {
+
+constexpr int kWave = 64;
+
+// Storage element types.  bf16 is handled as raw bits: the upper half of an fp32.
+struct bf16_t {
+  uint16_t bits;
+};
+
+template <typename T>
+struct Pack16;  // one 16-byte vector of T, unpacked to fp32
+
+template <>
+struct Pack16<float> {
+  static constexpr int kElts = 4;
+  __device__ static inline void load(const float* p, float (&f)[4]) {
+    const float4 v = *reinterpret_cast<const float4*>(p);
+    f[0] = v.x;
+    f[1] = v.y;
+    f[2] = v.z;
+    f[3] = v.w;
+  }
+};
+
+template <>
+struct Pack16<bf16_t> {
+  static constexpr int kElts = 8;
+  __device__ static inline void load(const bf16_t* p, float (&f)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    f[0] = __uint_as_float(v.x << 16);
+    f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    f[2] = __uint_as_float(v.y << 16);
+    f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+    f[4] = __uint_as_float(v.z << 16);
+    f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+    f[6] = __uint_as_float(v.w << 16);
+    f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+  }
+};
+
+__device__ inline float to_float(float x) { return x; }
+__device__ inline float to_float(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.bits) << 16); }
+
+// fp32 -> bf16, round to nearest even (NaN stays NaN).
+__device__ inline uint16_t f32_to_bf16_rne(float f) {
+  uint32_t b = __float_as_uint(f);
+  if ((b & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((b >> 16) | 0x0040u);
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return static_cast<uint16_t>(b >> 16);
+}
+
+__device__ inline void store_elt(float* p, float v) { *p = v; }
+__device__ inline void store_elt(bf16_t* p, float v) { p->bits = f32_to_bf16_rne(v); }
+
+// Order-preserving map from a score to an unsigned key: a larger score gives a larger key.
+// NaN ranks with -inf and -0 equals +0 (selection policy).  The smallest key a real score can
+// produce is 0x007FFFFF (-inf), so key 0 is free to mark "not a candidate".
+__device__ inline uint32_t score_key(float s) {
+  uint32_t b = __float_as_uint(s);
+  if ((b & 0x7FFFFFFFu) > 0x7F800000u) b = 0xFF800000u;
+  if (b == 0x80000000u) b = 0u;
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Radix levels of the selection: 11 + 11 + 10 bits, most significant first.
+constexpr int kBins1 = 2048;
+constexpr int kShift1 = 21;
+constexpr int kBins2 = 2048;
+constexpr int kShift2 = 10;
+constexpr int kBins3 = 1024;
+
+__device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }
+
+// Inclusive prefix sum across the 64 lanes of a wave.
+template <typename T>
+__device__ inline T wave_incl_scan(T v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    T o = __shfl_up(v, off, kWave);
+    if (lane >= off) v += o;
+  }
+  return v;
+}
+
+template <typename T>
+__device__ inline T wave_sum(T v) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// Exclusive prefix sum over the threads of a block of NWAVES waves (thread order).
+// s_tmp needs NWAVES + 1 entries.  Ends with a barrier, so s_tmp may be reused right away
+// for another scan.  `total` receives the block-wide sum.
+template <int NWAVES, typename T>
+__device__ inline T block_excl_scan(T v, T* s_tmp, T& total) {
+  const int lane = lane_id();
+  const int wave = threadIdx.x / kWave;
+  const T incl = wave_incl_scan(v);
+  if (lane == kWave - 1) s_tmp[wave] = incl;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    T run = 0;
+    for (int w = 0; w < NWAVES; ++w) {
+      const T t = s_tmp[w];
+      s_tmp[w] = run;
+      run += t;
+    }
+    s_tmp[NWAVES] = run;
+  }
+  __syncthreads();
+  const T base = s_tmp[wave];
+  total = s_tmp[NWAVES];
+  __syncthreads();
+  return base + incl - v;
+}
+
+}  // namespace tb

@@ -1,0 +1,89 @@
+// Host-side declarations shared by the translation units of libtokenbutler: one launcher per
+// kernel family, the workspace layout and the launch plan of the split attention.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "tokenbutler.h"
+
+namespace tb {
+
+constexpr int kHistBinsHost = 2048;  // level-1 histogram bins per (b,h) kept in the workspace
+constexpr int64_t kSelectMaxN = 1 << 20;
+
+// Workspace layout (byte offsets), fixed by B*Hq so that all operations agree on it:
+//   [0, cnt_bytes)             uint32 arrival counters, one per (b,h)      -- zero between calls
+//   [hist_off, part_off)       uint32 level-1 histograms [B*Hq][2048]      -- zero between calls
+//   [part_off, ...)            fp32 split-attention partials [B*Hq][nsplit][D+2]
+struct WsLayout {
+  size_t hist_off, part_off, total;
+};
+
+struct AttnPlan {
+  int rows_per_wg;  // list entries handled by one workgroup
+  int nsplit;       // workgroups per (b,h)
+};
+
+AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg);
+WsLayout ws_layout(int64_t units, int D, int nsplit);
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct ScoreLaunch {
+  const tb_cache_desc* desc;
+  const void* q_imp;
+  const void* Kimp;
+  float scale;
+  float* scores;
+  int64_t score_stride;
+  uint32_t* hist;  // nullptr: no histogram
+  int32_t lo, hi;  // candidate range for the histogram
+};
+tb_status launch_score(const ScoreLaunch& a, hipStream_t st);
+
+struct SelectLaunch {
+  int64_t units;
+  int64_t N;
+  const float* scores;
+  int64_t score_stride;
+  int32_t kk, lo, hi;
+  int32_t* idx;
+  int32_t* count;
+  int64_t idx_cap;
+  uint32_t* hist;
+  bool hist_ready;  // level-1 histogram already accumulated by the scoring kernel
+};
+tb_status launch_select(const SelectLaunch& a, hipStream_t st);
+
+struct AttnLaunch {
+  const tb_cache_desc* desc;
+  const void* q;
+  const void* K;
+  const void* V;
+  const int32_t* idx;
+  const int32_t* count;
+  int64_t idx_cap, max_count, tail_begin, tail_end;
+  float sm_scale;
+  float* out;
+  float* lse;
+  float* partials;
+  uint32_t* counters;
+  AttnPlan plan;
+};
+int attn_tile_rows_per_wg(int dtype, int D);
+tb_status launch_attn(const AttnLaunch& a, hipStream_t st);
+
+tb_status launch_project(const tb_cache_desc* d, const void* K, const void* W, int32_t Hw, void* Kimp,
+                         int64_t n_begin, int64_t n_end, hipStream_t st);
+
+tb_status launch_expand(int64_t units, int64_t N, int32_t radius, int32_t mode, const int32_t* idx_in,
+                        const int32_t* count_in, int64_t cap_in, int32_t* idx_out, int32_t* count_out,
+                        int64_t cap_out, hipStream_t st);
+
+tb_status launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+
+inline tb_status hip_status(hipError_t e) { return e == hipSuccess ? TB_OK : TB_ERR_HIP; }
+
+}  // namespace tb

@@ -1,0 +1,168 @@
+// Importance scoring: scores[b,h,n] = scale * <q_imp[b,h,:], K_imp[b,h/g,n,:]>.
+//
+// Bandwidth-bound stream over the projected-key cache.  A projected row is Dimp*sizeof(T)
+// bytes (64 B for the Llama-shaped configs); LPR = row_bytes/16 adjacent lanes each take one
+// 128-bit load of a row, so a wave instruction reads 1 KiB of consecutive memory.  Every
+// loaded row is used for all g query heads of its KV head (the cache is read once per KV
+// head).  Each thread issues all of its loads before consuming any of them.
+//
+// Optionally the kernel also accumulates the first radix level of the selection: a per-head
+// histogram of the top 11 bits of the order-preserving score key, built in LDS per workgroup
+// and flushed with one global atomic per non-empty bin.
+#include "tb_device.h"
+#include "tb_internal.h"
+
+namespace tb {
+namespace {
+
+constexpr int kScoreThreads = 1024;
+constexpr int kLoadsPerThread = 4;
+
+struct ScoreArgs {
+  const void* q_imp;
+  const void* Kimp;
+  float* scores;
+  uint32_t* hist;
+  int64_t N;
+  int64_t ki_stride_b, ki_stride_h, ki_stride_n;
+  int64_t score_stride;
+  int32_t Hq;
+  int32_t lo, hi;
+  float scale;
+};
+
+template <typename T, int DIMP, int G, bool HIST>
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
+  constexpr int EPL = Pack16<T>::kElts;      // elements per lane (one 128-bit load)
+  constexpr int LPR = DIMP / EPL;            // lanes per projected row
+  constexpr int RPP = kScoreThreads / LPR;   // rows per pass of the workgroup
+  constexpr int RW = RPP * kLoadsPerThread;  // rows per workgroup
+  static_assert(LPR >= 1 && LPR <= 16 && (LPR & (LPR - 1)) == 0, "row must span 1..16 lanes");
+
+  __shared__ uint32_t s_hist[HIST ? G * kBins1 : 1];
+
+  const int tid = threadIdx.x;
+  const int part = tid % LPR;
+  const int rsub = tid / LPR;
+  const int b = blockIdx.z;
+  const int hkv = blockIdx.y;
+  const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RW;
+
+  if (HIST) {
+    for (int i = tid; i < G * kBins1; i += kScoreThreads) s_hist[i] = 0;
+  }
+
+  const T* kbase = static_cast<const T*>(a.Kimp) + b * a.ki_stride_b + hkv * a.ki_stride_h + part * EPL;
+
+  // issue every load of this thread first
+  float kv[kLoadsPerThread][EPL];
+#pragma unroll
+  for (int i = 0; i < kLoadsPerThread; ++i) {
+    const int64_t row = row0 + i * RPP + rsub;
+    if (row < a.N) {
+      Pack16<T>::load(kbase + row * a.ki_stride_n, kv[i]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) kv[i][e] = 0.f;
+    }
+  }
+
+  // this lane's slice of the g importance queries
+  float qv[G][EPL];
+  const T* qbase = static_cast<const T*>(a.q_imp) + (static_cast<int64_t>(b) * a.Hq + hkv * G) * DIMP + part * EPL;
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh) Pack16<T>::load(qbase + hh * DIMP, qv[hh]);
+
+  if (HIST) __syncthreads();
+
+  float* sbase = a.scores + (static_cast<int64_t>(b) * a.Hq + hkv * G) * a.score_stride;
+#pragma unroll
+  for (int i = 0; i < kLoadsPerThread; ++i) {
+    const int64_t row = row0 + i * RPP + rsub;
+    float acc[G];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s = fmaf(qv[hh][e], kv[i][e], s);
+#pragma unroll
+      for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off, kWave);
+      acc[hh] = s * a.scale;
+    }
+    if (row < a.N) {
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh) {
+        if ((hh % LPR) == part) {
+          sbase[hh * a.score_stride + row] = acc[hh];
+          if (HIST && row >= a.lo && row < a.hi) atomicAdd(&s_hist[hh * kBins1 + (score_key(acc[hh]) >> kShift1)], 1u);
+        }
+      }
+    }
+  }
+
+  if (HIST) {
+    __syncthreads();
+    uint32_t* gh = a.hist + (static_cast<int64_t>(b) * a.Hq + hkv * G) * kBins1;
+    for (int i = tid; i < G * kBins1; i += kScoreThreads) {
+      const uint32_t c = s_hist[i];
+      if (c) atomicAdd(&gh[i], c);
+    }
+  }
+}
+
+template <typename T, int DIMP, int G>
+tb_status launch_tdg(const ScoreLaunch& L, hipStream_t st) {
+  const tb_cache_desc& d = *L.desc;
+  constexpr int EPL = Pack16<T>::kElts;
+  constexpr int RW = kScoreThreads / (DIMP / EPL) * kLoadsPerThread;
+  ScoreArgs a;
+  a.q_imp = L.q_imp;
+  a.Kimp = L.Kimp;
+  a.scores = L.scores;
+  a.hist = L.hist;
+  a.N = d.N;
+  a.ki_stride_b = d.ki_stride_b;
+  a.ki_stride_h = d.ki_stride_h;
+  a.ki_stride_n = d.ki_stride_n;
+  a.score_stride = L.score_stride;
+  a.Hq = d.Hq;
+  a.lo = L.lo;
+  a.hi = L.hi;
+  a.scale = L.scale;
+  if (d.N == 0) return TB_OK;
+  dim3 grid(static_cast<unsigned>((d.N + RW - 1) / RW), d.Hkv, d.B);
+  if (L.hist)
+    hipLaunchKernelGGL((score_kernel<T, DIMP, G, true>), grid, dim3(kScoreThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL((score_kernel<T, DIMP, G, false>), grid, dim3(kScoreThreads), 0, st, a);
+  return hip_status(hipGetLastError());
+}
+
+template <typename T, int DIMP>
+tb_status launch_td(const ScoreLaunch& L, hipStream_t st) {
+  switch (L.desc->Hq / L.desc->Hkv) {
+    case 1: return launch_tdg<T, DIMP, 1>(L, st);
+    case 2: return launch_tdg<T, DIMP, 2>(L, st);
+    case 4: return launch_tdg<T, DIMP, 4>(L, st);
+    case 8: return launch_tdg<T, DIMP, 8>(L, st);
+    default: return TB_ERR_UNSUPPORTED;
+  }
+}
+
+template <typename T>
+tb_status launch_t(const ScoreLaunch& L, hipStream_t st) {
+  switch (L.desc->Dimp) {
+    case 16: return launch_td<T, 16>(L, st);
+    case 32: return launch_td<T, 32>(L, st);
+    case 64: return launch_td<T, 64>(L, st);
+    default: return TB_ERR_UNSUPPORTED;
+  }
+}
+
+}  // namespace
+
+tb_status launch_score(const ScoreLaunch& L, hipStream_t st) {
+  return L.desc->dtype == TB_F32 ? launch_t<float>(L, st) : launch_t<bf16_t>(L, st);
+}
+
+}  // namespace tb

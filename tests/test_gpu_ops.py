@@ -1,0 +1,382 @@
+"""GPU parity: every exported operation, called through the C ABI, against the CPU oracle on
+the same bytes.  Sizes span several tiles and ragged tails; edge cases are listed per op.
+
+Bars: index lists bit-exact; scores within 1e-4 relative (with a magnitude guard for
+cancelled sums); attention within 1e-5 absolute (fp32) / 2e-2 absolute (bf16 K/V); projected
+keys within 1 unit in the last place of the storage type (fp32 accumulation against the
+oracle's fp64 accumulation can land on the other side of a rounding boundary)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import (DEV, dtype_name, gpu_attn, gpu_decode_step, gpu_expand, gpu_project, gpu_score, gpu_select,
+                      np_of, score_tolerance)
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def randn(shape, dtype, seed, scale=1.0):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return (torch.randn(shape, generator=g) * scale).to(dtype).to(DEV)
+
+
+# --------------------------------------------------------------------------- projection
+
+@pytest.mark.parametrize("dtype,D,Dimp,N,Hw", [
+    (torch.float32, 64, 16, 1000, 1),
+    (torch.bfloat16, 128, 32, 1037, 1),
+    (torch.bfloat16, 128, 32, 300, 3),
+    (torch.bfloat16, 64, 64, 129, 1),
+    (torch.float32, 128, 64, 65, 3),
+    (torch.bfloat16, 128, 16, 1, 1),
+])
+def test_project_keys(oracle, dtype, D, Dimp, N, Hw):
+    say(f"project dtype={dtype} D={D} Dimp={Dimp} N={N} Hw={Hw}")
+    B, Hkv = 2, 3
+    K = randn((B, Hkv, N + 5, D), dtype, 1)
+    W = randn((Hw, D, Dimp), dtype, 2, 1 / math.sqrt(D))
+    Kimp = gpu_project(K, W, N)
+    torch.cuda.synchronize()
+    dn = dtype_name(K)
+    ref = oracle.project_keys(np_of(K)[:, :, :N], np_of(W), dn)
+    got = np_of(Kimp)
+    assert not got[:, :, N:].any(), "rows beyond N must stay untouched"
+    if dn == "f32":
+        r64 = ref.astype(np.float64)
+        mag = np.einsum("bhnd,hdj->bhnj", np.abs(np_of(K)[:, :, :N]).astype(np.float64),
+                        np.abs(np.broadcast_to(np_of(W), (Hkv,) + W.shape[1:])).astype(np.float64))
+        assert np.all(np.abs(got[:, :, :N] - r64) <= 1e-5 * mag + 1e-30)
+    else:
+        g64, r64 = oracle.bf16_to_f64(got[:, :, :N]), oracle.bf16_to_f64(ref)
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(r64), 2.0 ** -126))) - 7)
+        assert np.all(np.abs(g64 - r64) <= ulp * 1.0000001)
+        assert np.mean(got[:, :, :N] == ref) > 0.99  # and nearly always the same bits
+
+
+def test_project_identity_and_row_range(oracle):
+    say("project identity W, row range")
+    B, Hkv, N, D, Dimp = 1, 2, 500, 128, 32
+    K = randn((B, Hkv, N, D), torch.bfloat16, 3)
+    W = torch.zeros((1, D, Dimp), dtype=torch.bfloat16, device=DEV)
+    W[0, :Dimp, :] = torch.eye(Dimp, dtype=torch.bfloat16)
+    Kimp = torch.full((B, Hkv, N, Dimp), 7.0, dtype=torch.bfloat16, device=DEV)
+    gpu_project(K, W, N, n_begin=70, n_end=391, Kimp=Kimp)
+    torch.cuda.synchronize()
+    assert torch.equal(Kimp[:, :, 70:391], K[:, :, 70:391, :Dimp])
+    assert torch.all(Kimp[:, :, :70] == 7.0) and torch.all(Kimp[:, :, 391:] == 7.0)
+
+
+def test_project_strided_cache(oracle):
+    say("project into a strided (over-allocated) cache")
+    B, Hkv, N, D, Dimp = 2, 2, 200, 128, 32
+    Kbig = randn((B, Hkv, 256, D + 8), torch.bfloat16, 4)
+    K = Kbig[:, :, :, :D]  # row stride D+8
+    W = randn((1, D, Dimp), torch.bfloat16, 5, 0.1)
+    Kimp_big = torch.zeros((B, Hkv, 256, Dimp + 8), dtype=torch.bfloat16, device=DEV)
+    Kimp = Kimp_big[:, :, :, :Dimp]
+    gpu_project(K, W, N, Kimp=Kimp)
+    torch.cuda.synchronize()
+    ref = oracle.bf16_to_f64(oracle.project_keys(np_of(K)[:, :, :N], np_of(W), "bf16"))
+    got = oracle.bf16_to_f64(np_of(Kimp)[:, :, :N])
+    assert np.allclose(got, ref, rtol=2 ** -7, atol=1e-30)
+    assert not np_of(Kimp_big)[..., Dimp:].any()
+
+
+# --------------------------------------------------------------------------- scoring
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,Dimp,N", [
+    (torch.float32, 1, 8, 8, 16, 1024),
+    (torch.bfloat16, 1, 32, 8, 32, 5000),
+    (torch.bfloat16, 2, 16, 2, 32, 1025),
+    (torch.bfloat16, 1, 4, 2, 16, 63),
+    (torch.float32, 1, 2, 2, 64, 300),
+    (torch.bfloat16, 1, 4, 4, 64, 1),
+    (torch.float32, 2, 8, 2, 32, 4097),
+])
+def test_score(oracle, dtype, B, Hq, Hkv, Dimp, N):
+    say(f"score dtype={dtype} B={B} Hq={Hq} Hkv={Hkv} Dimp={Dimp} N={N}")
+    q_imp = randn((B, Hq, Dimp), dtype, 6)
+    Kimp = randn((B, Hkv, N + 3, Dimp), dtype, 7)
+    scale = 0.7
+    s = gpu_score(q_imp, Kimp, N, scale)
+    torch.cuda.synchronize()
+    dn = dtype_name(Kimp)
+    ref = oracle.score(np_of(q_imp), np_of(Kimp)[:, :, :N], dn, scale)
+    got = np_of(s)
+    guard = score_tolerance(oracle, np_of(q_imp), np_of(Kimp)[:, :, :N], dn, scale, Hq // Hkv)
+    err = np.abs(got[:, :, :N].astype(np.float64) - ref)
+    assert np.all(err <= 1e-4 * np.abs(ref) + guard)
+    assert np.isnan(got[:, :, N:]).all(), "padding beyond N must stay untouched"
+
+
+# --------------------------------------------------------------------------- selection
+
+def check_select(oracle, scores_t, N, k, sink, window):
+    idx, cnt = gpu_select(scores_t, N, k, sink, window)
+    torch.cuda.synchronize()
+    s_np = np_of(scores_t)[:, :, :N]
+    ridx, rcnt = oracle.select_topk(s_np, k, sink, window)
+    gi, gc = np_of(idx), np_of(cnt)
+    assert np.array_equal(gc, rcnt)
+    width = ridx.shape[-1]
+    mask = np.arange(width)[None, None, :] < rcnt[..., None]
+    assert np.array_equal(np.where(mask, gi[..., :width], -1), np.where(mask, ridx, -1))
+    assert np.all(gi[..., :width][~mask] == -7), "entries beyond count must stay untouched"
+    return gi, gc
+
+
+@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 1000, 1025, 4096, 4097, 8192, 20000, 40000, 65536, 70001])
+def test_select_sizes_random_scores(oracle, N):
+    say(f"select random N={N}")
+    B, Hq = 2, 3
+    scores = randn((B, Hq, (N + 3) // 4 * 4), torch.float32, 100 + N)
+    for k in sorted({1, max(1, N // 10), N - 1, N, N + 5} - {0}):
+        check_select(oracle, scores, N, k, 0, 0)
+    if N > 20:
+        check_select(oracle, scores, N, max(1, N // 7), 5, 9)
+        check_select(oracle, scores, N, 0, 3, 4)
+
+
+@pytest.mark.parametrize("N", [777, 9000, 66000])
+def test_select_ties_and_special_values(oracle, N):
+    say(f"select ties/specials N={N}")
+    g = torch.Generator(device="cpu").manual_seed(N)
+    stride = (N + 3) // 4 * 4
+    # heavy ties: scores quantised to a handful of values, threshold lands inside a tie block
+    q = torch.randint(-3, 4, (1, 4, stride), generator=g).float() * 0.5
+    for k in (1, N // 3, N // 2, N - 1):
+        check_select(oracle, q.to(DEV), N, k, 0, 0)
+    check_select(oracle, q.to(DEV), N, N // 3, 17, 33)
+    # all equal
+    same = torch.full((1, 2, stride), 1.25)
+    check_select(oracle, same.to(DEV), N, N // 5, 0, 0)
+    check_select(oracle, same.to(DEV), N, N // 5, 11, 7)
+    # special values: +-inf, NaN (ranks with -inf), -0 / +0, denormals, huge and tiny magnitudes
+    sp = torch.randn((1, 3, stride), generator=g)
+    pos = torch.randperm(N, generator=g)
+    vals = [float("inf"), float("-inf"), float("nan"), -0.0, 0.0, 1e-42, -1e-42, 3e38, -3e38, 1e-30]
+    for i, v in enumerate(vals):
+        sp[:, :, pos[i::len(vals)][: max(1, N // 40)]] = v
+    for k in (1, N // 20, N // 2, N - 2):
+        check_select(oracle, sp.to(DEV), N, k, 0, 0)
+    # all NaN / all -inf mixture: index order decides
+    nn = torch.full((1, 1, stride), float("nan"))
+    nn[0, 0, ::3] = float("-inf")
+    check_select(oracle, nn.to(DEV), N, N // 2, 0, 0)
+    # sorted ascending and descending
+    asc = torch.arange(stride, dtype=torch.float32).view(1, 1, stride)
+    check_select(oracle, asc.to(DEV), N, N // 4, 0, 0)
+    check_select(oracle, (-asc).to(DEV), N, N // 4, 2, 2)
+    # values that agree in the top 11 and top 22 key bits: every radix level has to refine
+    base = torch.full((1, 2, stride), 1.0)
+    base = (base.view(torch.int32) + torch.randint(0, 700, (1, 2, stride), generator=g, dtype=torch.int32)).view(torch.float32)
+    check_select(oracle, base.to(DEV), N, N // 3, 0, 0)
+
+
+def test_select_sink_window_cover_everything(oracle):
+    say("select sink+window >= N")
+    N = 300
+    scores = randn((1, 2, 300), torch.float32, 9)
+    gi, gc = check_select(oracle, scores, N, 10, 200, 200)
+    assert np.all(gc == N)
+    gi, gc = check_select(oracle, scores, N, 10, 400, 0)
+    assert np.all(gc == N)
+
+
+def test_select_repeatable_and_workspace_reuse(oracle):
+    say("select repeated calls share one workspace")
+    from paper_2503_07518_amd import binding as tb
+    N, k = 30000, 3000
+    scores = randn((2, 8, N), torch.float32, 10)
+    d = tb.tb_cache_desc()
+    d.B, d.Hq, d.Hkv, d.D, d.Dimp, d.dtype, d.N = 2, 8, 8, 128, 32, tb.TB_F32, N
+    d.k_stride_n = d.v_stride_n = 128
+    d.ki_stride_n = 32
+    ws = tb.new_workspace(tb.TB_OP_SELECT, d)
+    first = None
+    for _ in range(4):
+        idx, cnt = gpu_select(scores, N, k, ws=ws)
+        torch.cuda.synchronize()
+        if first is None:
+            first = (idx.clone(), cnt.clone())
+        assert torch.equal(idx, first[0]) and torch.equal(cnt, first[1])
+    ridx, rcnt = oracle.select_topk(np_of(scores), k)
+    assert np.array_equal(np_of(first[0]), ridx) and np.array_equal(np_of(first[1]), rcnt)
+    assert not ws.any(), "the workspace is left zeroed"
+
+
+# --------------------------------------------------------------------------- neighbours
+
+def random_lists(B, Hq, N, count_max, seed, cap=None):
+    rng = np.random.default_rng(seed)
+    cap = cap or max(count_max, 1)
+    idx = np.full((B, Hq, cap), -1, np.int32)
+    cnt = np.zeros((B, Hq), np.int32)
+    for b in range(B):
+        for h in range(Hq):
+            c = int(rng.integers(0, count_max + 1)) if (b + h) % 3 else count_max
+            c = min(c, N)
+            idx[b, h, :c] = np.sort(rng.choice(N, c, replace=False))
+            cnt[b, h] = c
+    return idx, cnt
+
+
+@pytest.mark.parametrize("N,count_max,radius", [(50, 20, 1), (1000, 300, 1), (1000, 999, 2), (70000, 5000, 1),
+                                                (4096, 4096, 3), (10, 0, 1), (100000, 7, 5), (5000, 2500, 0)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_expand_neighbors(oracle, N, count_max, radius, mode):
+    say(f"expand N={N} count_max={count_max} r={radius} mode={mode}")
+    idx, cnt = random_lists(2, 3, N, count_max, seed=N + radius)
+    # clustered input as well: runs of consecutive positions and picks at both ends
+    if count_max >= 8 and N > 64:
+        run = np.arange(N - 6, N, dtype=np.int32)
+        idx[0, 0, :] = -1
+        head = np.array([0, 1, 2], np.int32)
+        mid = np.arange(N // 2, N // 2 + min(count_max - 9, 40), dtype=np.int32)
+        lst = np.concatenate([head, mid, run])
+        idx[0, 0, : len(lst)] = lst
+        cnt[0, 0] = len(lst)
+    out, oc = gpu_expand(torch.from_numpy(idx).to(DEV), torch.from_numpy(cnt).to(DEV), N, radius, mode)
+    torch.cuda.synchronize()
+    ro, rc = oracle.expand_neighbors(idx, cnt, N, radius, cap_out=out.shape[-1], mode=mode)
+    go, gc = np_of(out), np_of(oc)
+    assert np.array_equal(gc, rc)
+    mask = np.arange(go.shape[-1])[None, None, :] < rc[..., None]
+    assert np.array_equal(np.where(mask, go, -1), np.where(mask, ro, -1))
+    assert np.all(go[~mask] == -7)
+
+
+# --------------------------------------------------------------------------- attention
+
+ATTN_TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,D,N,count_max", [
+    (torch.float32, 1, 8, 8, 64, 1024, 128),
+    (torch.bfloat16, 1, 32, 8, 128, 5000, 700),
+    (torch.bfloat16, 2, 8, 2, 128, 3000, 3000),
+    (torch.float32, 1, 4, 2, 128, 777, 333),
+    (torch.bfloat16, 1, 4, 4, 64, 900, 65),
+    (torch.bfloat16, 1, 2, 2, 128, 40, 1),
+    (torch.bfloat16, 3, 16, 2, 128, 9000, 2049),
+])
+def test_sparse_decode_attn(oracle, dtype, B, Hq, Hkv, D, N, count_max):
+    say(f"attn dtype={dtype} B={B} Hq={Hq} Hkv={Hkv} D={D} N={N} count_max={count_max}")
+    q = randn((B, Hq, D), dtype, 11)
+    K = randn((B, Hkv, N + 2, D), dtype, 12)
+    V = randn((B, Hkv, N + 2, D), dtype, 13)
+    idx, cnt = random_lists(B, Hq, N, count_max, seed=14)
+    cnt[0, 0] = 0  # an empty list
+    sm = 1 / math.sqrt(D)
+    out, lse = gpu_attn(q, K, V, torch.from_numpy(idx).to(DEV), torch.from_numpy(cnt).to(DEV), N, sm)
+    torch.cuda.synchronize()
+    dn = dtype_name(K)
+    ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K)[:, :, :N], np_of(V)[:, :, :N], idx, cnt, dn, sm)
+    go, gl = np_of(out), np_of(lse)
+    assert np.abs(go - ro).max() <= ATTN_TOL[dn]
+    assert not go[0, 0].any() and gl[0, 0] == -np.inf
+    fin = np.isfinite(rl)
+    assert np.array_equal(np.isfinite(gl), fin)
+    assert np.abs(gl[fin] - rl[fin]).max() <= 1e-4
+
+
+def test_attn_full_budget_equals_dense_and_tail(oracle):
+    say("attn full list == dense; list + dense tail")
+    B, Hq, Hkv, D, N = 1, 8, 2, 128, 2500
+    q = randn((B, Hq, D), torch.bfloat16, 15)
+    K = randn((B, Hkv, N, D), torch.bfloat16, 16)
+    V = randn((B, Hkv, N, D), torch.bfloat16, 17)
+    sm = 1 / math.sqrt(D)
+    full = torch.arange(N, dtype=torch.int32, device=DEV).expand(B, Hq, N).contiguous()
+    cnt = torch.full((B, Hq), N, dtype=torch.int32, device=DEV)
+    out, _ = gpu_attn(q, K, V, full, cnt, N, sm)
+    torch.cuda.synchronize()
+    dense = oracle.dense_decode_attn(np_of(q), np_of(K), np_of(V), "bf16", sm)
+    assert np.abs(np_of(out) - dense).max() <= 2e-2
+    # a list over the first part plus the rest as a dense tail gives the same result
+    idx, c = random_lists(B, Hq, 2000, 300, seed=18)
+    out_t, lse_t = gpu_attn(q, K, V, torch.from_numpy(idx).to(DEV), torch.from_numpy(c).to(DEV), N, sm,
+                            tail=(2000, N))
+    torch.cuda.synchronize()
+    cap = idx.shape[-1] + (N - 2000)
+    joined = np.full((B, Hq, cap), -1, np.int32)
+    for h in range(Hq):
+        joined[0, h, : c[0, h]] = idx[0, h, : c[0, h]]
+        joined[0, h, c[0, h]: c[0, h] + N - 2000] = np.arange(2000, N)
+    ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K), np_of(V), joined, c + (N - 2000), "bf16", sm)
+    assert np.abs(np_of(out_t) - ro).max() <= 2e-2
+    assert np.abs(np_of(lse_t) - rl).max() <= 1e-4
+
+
+def test_attn_strided_cache_and_max_count_truncation(oracle):
+    say("attn on a strided cache view; max_count truncates longer lists")
+    B, Hq, Hkv, D, N = 2, 4, 2, 128, 1200
+    q = randn((B, Hq, D), torch.bfloat16, 19)
+    Kbig = randn((B, Hkv, N, 2 * D), torch.bfloat16, 20)
+    K, V = Kbig[..., :D], Kbig[..., D:]  # interleaved K|V rows, stride 2D
+    idx, cnt = random_lists(B, Hq, N, 500, seed=21)
+    sm = 0.1
+    out, lse = gpu_attn(q, K, V, torch.from_numpy(idx).to(DEV), torch.from_numpy(cnt).to(DEV), N, sm, max_count=260)
+    torch.cuda.synchronize()
+    ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K), np_of(V), idx, np.minimum(cnt, 260), "bf16", sm)
+    assert np.abs(np_of(out) - ro).max() <= 2e-2
+
+
+def test_attn_repeatable(oracle):
+    say("attn: repeated runs are bit-identical (fixed merge order)")
+    B, Hq, Hkv, D, N = 1, 32, 8, 128, 20000
+    q = randn((B, Hq, D), torch.bfloat16, 22)
+    K = randn((B, Hkv, N, D), torch.bfloat16, 23)
+    V = randn((B, Hkv, N, D), torch.bfloat16, 24)
+    idx, cnt = random_lists(B, Hq, N, 2000, seed=25)
+    ti, tc = torch.from_numpy(idx).to(DEV), torch.from_numpy(cnt).to(DEV)
+    from paper_2503_07518_amd import binding as tb
+    d = tb.make_desc(N, Hq, K=K, V=V)
+    ws = tb.new_workspace(tb.TB_OP_ATTN, d, 2000)
+    ref = None
+    for _ in range(5):
+        out, lse = gpu_attn(q, K, V, ti, tc, N, 0.09, ws=ws)
+        torch.cuda.synchronize()
+        if ref is None:
+            ref = (out.clone(), lse.clone())
+        assert torch.equal(out, ref[0]) and torch.equal(lse, ref[1])
+
+
+# --------------------------------------------------------------------------- fused step
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,D,Dimp,N,k,sink,window", [
+    (torch.float32, 1, 8, 8, 64, 16, 1024, 128, 0, 0),
+    (torch.bfloat16, 1, 32, 8, 128, 32, 6000, 600, 0, 0),
+    (torch.bfloat16, 2, 16, 2, 128, 32, 3001, 300, 16, 32),
+    (torch.bfloat16, 1, 8, 2, 128, 32, 500, 500, 0, 0),
+    (torch.bfloat16, 1, 8, 2, 128, 32, 500, 0, 4, 4),
+])
+def test_decode_step_matches_separate_calls_and_oracle(oracle, dtype, B, Hq, Hkv, D, Dimp, N, k, sink, window):
+    say(f"decode_step dtype={dtype} B={B} Hq={Hq} Hkv={Hkv} D={D} Dimp={Dimp} N={N} k={k} S={sink} W={window}")
+    q = randn((B, Hq, D), dtype, 26)
+    q_imp = randn((B, Hq, Dimp), dtype, 27)
+    K = randn((B, Hkv, N, D), dtype, 28)
+    V = randn((B, Hkv, N, D), dtype, 29)
+    W = randn((1, D, Dimp), dtype, 30, 1 / math.sqrt(D))
+    Kimp = gpu_project(K, W, N)
+    sm = 1 / math.sqrt(D)
+    s, idx, cnt, out, lse = gpu_decode_step(q, q_imp, K, V, Kimp, N, k, sink, window, sm)
+    s2 = gpu_score(q_imp, Kimp, N)
+    idx2, cnt2 = gpu_select(s2, N, k, sink, window, Hkv=Hkv)
+    out2, lse2 = gpu_attn(q, K, V, idx2, cnt2, N, sm, max_count=idx2.shape[-1])
+    torch.cuda.synchronize()
+    assert torch.equal(s[:, :, :N], s2[:, :, :N])
+    assert torch.equal(cnt, cnt2) and torch.equal(idx, idx2)
+    assert torch.equal(out, out2) and torch.equal(lse, lse2)
+    dn = dtype_name(K)
+    ridx, rcnt = oracle.select_topk(np_of(s)[:, :, :N], k, sink, window)
+    assert np.array_equal(np_of(cnt), rcnt)
+    assert np.array_equal(np_of(idx)[..., : ridx.shape[-1]], ridx)
+    ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K), np_of(V), np_of(idx), np_of(cnt), dn, sm)
+    assert np.abs(np_of(out) - ro).max() <= ATTN_TOL[dn]
