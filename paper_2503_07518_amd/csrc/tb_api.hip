@@ -4,6 +4,10 @@
 
 namespace tb {
 
+#ifndef TB_ATTN_TARGET_WGS
+#define TB_ATTN_TARGET_WGS 1024
+#endif
+
 AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
   // Aim for a few workgroups per compute unit (256 CUs) so that the gathers of the whole
   // chip are in flight together; a workgroup takes whole wave tiles.
@@ -13,7 +17,7 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
     p.nsplit = 1;
     return p;
   }
-  const int64_t target_wgs = 1024;
+  const int64_t target_wgs = TB_ATTN_TARGET_WGS;
   int64_t want = (target_wgs + units - 1) / units;
   const int64_t max_split = (max_rows + tile_rows_per_wg - 1) / tile_rows_per_wg;
   if (want > max_split) want = max_split;
@@ -27,7 +31,7 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
 
 WsLayout ws_layout(int64_t units, int D, int nsplit) {
   WsLayout w;
-  w.hist_off = align_up(static_cast<size_t>(units) * sizeof(uint32_t), 256);
+  w.hist_off = align_up(static_cast<size_t>(units) * kCounterStrideWords * sizeof(uint32_t), 256);
   w.part_off = w.hist_off + align_up(static_cast<size_t>(units) * kHistBinsHost * sizeof(uint32_t), 256);
   w.total = w.part_off + align_up(static_cast<size_t>(units) * nsplit * (D + 2) * sizeof(float), 256);
   return w;
@@ -115,6 +119,10 @@ tb_status check_attn_args(const tb_cache_desc* d, const void* q, const void* K, 
   TB_TRY(check_strides(d, d->v_stride_b, d->v_stride_h, d->v_stride_n, d->D));
   if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return TB_ERR_UNSUPPORTED;
   if (max_count + (tail_end - tail_begin) > (int64_t{1} << 30)) return TB_ERR_UNSUPPORTED;
+  // the gather addresses rows with 32-bit byte offsets inside one (b, kv-head) slab
+  const int64_t elt = d->dtype == TB_F32 ? 4 : 2;
+  if (d->N * d->k_stride_n * elt >= (int64_t{1} << 32) || d->N * d->v_stride_n * elt >= (int64_t{1} << 32))
+    return TB_ERR_UNSUPPORTED;
   return TB_OK;
 }
 

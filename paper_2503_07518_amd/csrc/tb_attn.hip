@@ -10,7 +10,8 @@
 // accumulator slice of D/LPR elements) in the base-2 domain; groups are merged by wave
 // shuffles, waves through LDS, and workgroups through fp32 partials in the workspace: the
 // last workgroup of a head to arrive (device-scope counter) combines the partials in split
-// order, so the result does not depend on arrival order.
+// order, so the result does not depend on arrival order.  The counter is reset by that
+// workgroup, which leaves the workspace ready for the next call.
 #include "tb_device.h"
 #include "tb_internal.h"
 
@@ -19,7 +20,15 @@ namespace {
 
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = kAttnThreads / kWave;
-constexpr int kLoadsPerTile = 8;
+#ifndef TB_ATTN_LOADS_PER_TILE
+#define TB_ATTN_LOADS_PER_TILE 8
+#endif
+constexpr int kLoadsPerTile = TB_ATTN_LOADS_PER_TILE;
+// occupancy the register allocation is held to: 4 waves per SIMD = 4 workgroups per CU, so that a
+// launch of up to 1024 workgroups is resident at once (no second round of workgroups)
+#ifndef TB_ATTN_WAVES_PER_SIMD
+#define TB_ATTN_WAVES_PER_SIMD 4
+#endif
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -43,7 +52,7 @@ struct AttnArgs {
 __device__ inline float exp2_safe(float d) { return __builtin_amdgcn_exp2f(d); }
 
 template <typename T, int D>
-__global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_kernel(AttnArgs a) {
   constexpr int EPL = Pack16<T>::kElts;    // elements per lane
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int GPW = kWave / LPR;         // row groups per wave
@@ -65,18 +74,18 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   const int64_t u = static_cast<int64_t>(b) * a.Hq + h;
   const int hkv = h / a.g;
 
-  int64_t cnt = a.count[u];
-  cnt = cnt < 0 ? 0 : (cnt > a.max_count ? a.max_count : cnt);
-  const int64_t total = cnt + (a.tail_end - a.tail_begin);
-
   const int64_t wg_beg = static_cast<int64_t>(split) * a.rows_per_wg;
   const int rows_per_wave = a.rows_per_wg / kAttnWaves;
-  int64_t w_beg = wg_beg + static_cast<int64_t>(wave) * rows_per_wave;
-  int64_t w_end = w_beg + rows_per_wave;
-  if (w_end > total) w_end = total;
+  const int64_t w_beg0 = wg_beg + static_cast<int64_t>(wave) * rows_per_wave;
+  const int64_t w_beg = w_beg0;
+  int64_t cnt, total, w_end;  // set once the count has arrived (first-tile block below)
 
-  const T* kbase = static_cast<const T*>(a.K) + b * a.k_stride_b + hkv * a.k_stride_h + sub * EPL;
-  const T* vbase = static_cast<const T*>(a.V) + b * a.v_stride_b + hkv * a.v_stride_h + sub * EPL;
+  const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.K) + b * a.k_stride_b +
+                                                   hkv * a.k_stride_h) + sub * 16;
+  const char* vbase = reinterpret_cast<const char*>(static_cast<const T*>(a.V) + b * a.v_stride_b +
+                                                   hkv * a.v_stride_h) + sub * 16;
+  const uint32_t k_row_bytes = static_cast<uint32_t>(a.k_stride_n * sizeof(T));
+  const uint32_t v_row_bytes = static_cast<uint32_t>(a.v_stride_n * sizeof(T));
   const int32_t* list = a.idx + u * a.idx_cap;
 
   float qv[EPL];
@@ -89,34 +98,60 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-  for (int64_t t0 = w_beg; t0 < w_end; t0 += TILE) {
-    // lanes 0..TILE-1 fetch the row numbers of this tile (selected list, then the dense tail)
-    int32_t n_mine = -1;
-    {
-      const int64_t i = t0 + lane;
-      if (lane < TILE && i < w_end) {
-        int64_t n = (i < cnt) ? static_cast<int64_t>(list[i]) : a.tail_begin + (i - cnt);
-        n = n < 0 ? 0 : (n >= a.N ? a.N - 1 : n);  // keep the gather inside the cache whatever the list holds
-        n_mine = static_cast<int32_t>(n);
-      }
+  // row numbers of a tile: lanes 0..TILE-1 fetch one entry each (selected list, then the
+  // dense tail); -1 marks a slot past the end.  The next tile's entries are fetched while the
+  // current tile is being processed.
+  auto fetch_rows = [&](int64_t t0) -> int32_t {
+    const int64_t i = t0 + lane;
+    if (lane < TILE && i < w_end) {
+      int64_t n = (i < cnt) ? static_cast<int64_t>(list[i]) : a.tail_begin + (i - cnt);
+      n = n < 0 ? 0 : (n >= a.N ? a.N - 1 : n);  // keep the gather inside the cache whatever the list holds
+      return static_cast<int32_t>(n);
     }
-    float kv[kLoadsPerTile][EPL], vv[kLoadsPerTile][EPL];
+    return -1;
+  };
+  int32_t n_next;
+  {
+    // first tile: the list entry is read without waiting for the count (the slot is inside
+    // the list's capacity whatever the count is) and sorted out afterwards
+    const int64_t i = w_beg0 + lane;
+    const int64_t i_safe = (i < a.idx_cap) ? i : (a.idx_cap > 0 ? a.idx_cap - 1 : 0);
+    const int32_t raw = (lane < TILE && a.idx_cap > 0) ? list[i_safe] : 0;
+    int64_t cnt_now = a.count[u];
+    cnt_now = cnt_now < 0 ? 0 : (cnt_now > a.max_count ? a.max_count : cnt_now);
+    cnt = cnt_now;
+    total = cnt + (a.tail_end - a.tail_begin);
+    w_end = (w_beg0 + rows_per_wave < total) ? w_beg0 + rows_per_wave : total;
+    int64_t n = (i < cnt) ? static_cast<int64_t>(raw) : a.tail_begin + (i - cnt);
+    n = n < 0 ? 0 : (n >= a.N ? a.N - 1 : n);
+    n_next = (lane < TILE && i < w_end) ? static_cast<int32_t>(n) : -1;
+  }
+  for (int64_t t0 = w_beg; t0 < w_end; t0 += TILE) {
+    const int32_t n_mine = n_next;
+    typename Pack16<T>::Raw kraw[kLoadsPerTile], vraw[kLoadsPerTile];  // kept packed until used
     bool valid[kLoadsPerTile];
 #pragma unroll
     for (int t = 0; t < kLoadsPerTile; ++t) {
       const int32_t n = __shfl(n_mine, t * GPW + grp, kWave);
       valid[t] = n >= 0;
-      const int64_t row = valid[t] ? n : 0;
-      Pack16<T>::load(kbase + row * a.k_stride_n, kv[t]);
-      Pack16<T>::load(vbase + row * a.v_stride_n, vv[t]);
+      const uint32_t row = valid[t] ? static_cast<uint32_t>(n) : 0u;
+      // 32-bit byte offsets from a per-workgroup base (the host checks that a head's slab is
+      // below 4 GiB): one address register per gather instead of two
+      kraw[t] = Pack16<T>::load_raw(kbase + row * k_row_bytes);
+      vraw[t] = Pack16<T>::load_raw(vbase + row * v_row_bytes);
     }
+    n_next = fetch_rows(t0 + TILE);
+    // every gather of the tile is in flight before the first one is consumed
+    __builtin_amdgcn_sched_barrier(0);
     float sc[kLoadsPerTile];
     float tmax = -INFINITY;
 #pragma unroll
     for (int t = 0; t < kLoadsPerTile; ++t) {
+      float kf[EPL];
+      Pack16<T>::unpack(kraw[t], kf);
       float s = 0.f;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kv[t][e], s);
+      for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kf[e], s);
 #pragma unroll
       for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off, kWave);
       sc[t] = valid[t] ? s : -INFINITY;
@@ -132,8 +167,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
       for (int t = 0; t < kLoadsPerTile; ++t) {
         const float p = exp2_safe(sc[t] - m_new);  // invalid -> 0
         l += p;
+        float vf[EPL];
+        Pack16<T>::unpack(vraw[t], vf);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vv[t][e], acc[e]);
+        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
       }
       m = m_new;
     }
@@ -182,42 +219,88 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
 
   if (a.nsplit == 1) {
     if (tid < D) a.out[u * D + tid] = (L > 0.f) ? o / L : 0.f;
-    if (tid == 0 && a.lse) a.lse[u] = (L > 0.f) ? M * kLn2 + __logf(L) : -INFINITY;
+    if (tid == 0 && a.lse) a.lse[u] = (L > 0.f) ? M * kLn2 + logf(L) : -INFINITY;
     return;
   }
 
-  // several workgroups per head: publish the partial, the last one to arrive combines
+  // Several workgroups per head: publish the partial, the last one to arrive combines.
+  // Partials are written and read with device-scope atomic accesses (they go to the memory
+  // side of the per-XCD L2 caches), so the hand-over needs no cache write-back or invalidate:
+  // the stores have completed when the barrier is passed, then the ticket is taken.
   float* part = a.partials + (u * a.nsplit + split) * (D + 2);
-  if (tid < D) part[tid] = o;
+  if (tid < D) __hip_atomic_store(&part[tid], o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (tid == 0) {
-    part[D] = M;
-    part[D + 1] = L;
+    __hip_atomic_store(&part[D], M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&part[D + 1], L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  __threadfence();
   __syncthreads();
   if (tid == 0) {
-    const uint32_t ticket = __hip_atomic_fetch_add(&a.counters[u], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t ticket = __hip_atomic_fetch_add(&a.counters[u * kCounterStrideWords], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (ticket == static_cast<uint32_t>(a.nsplit - 1)) ? 1u : 0u;
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
-  if (tid < D) {
+  // Combine the partials: thread (d, lane-group j) walks splits j, j+G, ... in chunks whose
+  // loads are all issued before the first is used (a dependent chain of device-scope loads
+  // would cost one memory round trip per split); the G groups are then merged through LDS in
+  // group order.  The order of combination is fixed, so the result is reproducible.
+  {
+    constexpr int G = kAttnThreads / D;  // split groups: 2 for D=128, 4 for D=64
+    constexpr int CH = 8;                // loads in flight per thread and field
+    const int d = tid % D, j = tid / D;
     const float* p0 = a.partials + u * a.nsplit * (D + 2);
-    float Mg = -INFINITY;
-    for (int s = 0; s < a.nsplit; ++s) Mg = fmaxf(Mg, p0[s * (D + 2) + D]);
-    float Lg = 0.f, og = 0.f;
-    if (Mg > -INFINITY) {
-      for (int s = 0; s < a.nsplit; ++s) {
-        const float wgt = exp2_safe(p0[s * (D + 2) + D] - Mg);
-        Lg += p0[s * (D + 2) + D + 1] * wgt;
-        og += p0[s * (D + 2) + tid] * wgt;
+    float Mg = -INFINITY, Lg = 0.f, og = 0.f;
+    for (int s0 = j; s0 < a.nsplit; s0 += G * CH) {
+      float mv[CH], lv[CH], ov[CH];
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int sp = s0 + c * G;
+        const int sl = sp < a.nsplit ? sp : a.nsplit - 1;
+        mv[c] = __hip_atomic_load(&p0[sl * (D + 2) + D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lv[c] = __hip_atomic_load(&p0[sl * (D + 2) + D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ov[c] = __hip_atomic_load(&p0[sl * (D + 2) + d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (sp >= a.nsplit) {
+          mv[c] = -INFINITY;
+          lv[c] = 0.f;
+          ov[c] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const float Mn = fmaxf(Mg, mv[c]);
+        if (Mn > -INFINITY) {
+          const float wa = exp2_safe(Mg - Mn), wb = exp2_safe(mv[c] - Mn);
+          Lg = Lg * wa + lv[c] * wb;
+          og = og * wa + ov[c] * wb;
+          Mg = Mn;
+        }
       }
     }
-    a.out[u * D + tid] = (Lg > 0.f) ? og / Lg : 0.f;
-    if (tid == 0 && a.lse) a.lse[u] = (Lg > 0.f) ? Mg * kLn2 + __logf(Lg) : -INFINITY;
+    __syncthreads();  // s_acc / s_m / s_l were last read before the partial was published
+    s_acc[j][d] = og;
+    if (d == 0) {
+      s_m[j] = Mg;
+      s_l[j] = Lg;
+    }
+    __syncthreads();
+    if (tid < D) {
+      float Mt = -INFINITY;
+#pragma unroll
+      for (int jj = 0; jj < G; ++jj) Mt = fmaxf(Mt, s_m[jj]);
+      float Lt = 0.f, ot = 0.f;
+      if (Mt > -INFINITY) {
+#pragma unroll
+        for (int jj = 0; jj < G; ++jj) {
+          const float wgt = exp2_safe(s_m[jj] - Mt);
+          Lt += s_l[jj] * wgt;
+          ot += s_acc[jj][tid] * wgt;
+        }
+      }
+      a.out[u * D + tid] = (Lt > 0.f) ? ot / Lt : 0.f;
+      if (tid == 0 && a.lse) a.lse[u] = (Lt > 0.f) ? Mt * kLn2 + logf(Lt) : -INFINITY;
+    }
   }
-  if (tid == 0) __hip_atomic_store(&a.counters[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) __hip_atomic_store(&a.counters[u * kCounterStrideWords], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <typename T, int D>

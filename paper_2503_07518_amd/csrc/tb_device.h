@@ -20,6 +20,14 @@ struct Pack16;  // one 16-byte vector of T, unpacked to fp32
 template <>
 struct Pack16<float> {
   static constexpr int kElts = 4;
+  using Raw = float4;
+  __device__ static inline Raw load_raw(const void* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static inline void unpack(const Raw& v, float (&f)[4]) {
+    f[0] = v.x;
+    f[1] = v.y;
+    f[2] = v.z;
+    f[3] = v.w;
+  }
   __device__ static inline void load(const float* p, float (&f)[4]) {
     const float4 v = *reinterpret_cast<const float4*>(p);
     f[0] = v.x;
@@ -32,6 +40,18 @@ struct Pack16<float> {
 template <>
 struct Pack16<bf16_t> {
   static constexpr int kElts = 8;
+  using Raw = uint4;
+  __device__ static inline Raw load_raw(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+  __device__ static inline void unpack(const Raw& v, float (&f)[8]) {
+    f[0] = __uint_as_float(v.x << 16);
+    f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    f[2] = __uint_as_float(v.y << 16);
+    f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+    f[4] = __uint_as_float(v.z << 16);
+    f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+    f[6] = __uint_as_float(v.w << 16);
+    f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+  }
   __device__ static inline void load(const bf16_t* p, float (&f)[8]) {
     const uint4 v = *reinterpret_cast<const uint4*>(p);
     f[0] = __uint_as_float(v.x << 16);

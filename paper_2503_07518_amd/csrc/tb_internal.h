@@ -12,9 +12,15 @@ namespace tb {
 
 constexpr int kHistBinsHost = 2048;  // level-1 histogram bins per (b,h) kept in the workspace
 constexpr int64_t kSelectMaxN = 1 << 20;
+// Arrival counters sit 256 bytes apart so that the device-scope atomics of different heads do
+// not queue up on one cache line / memory channel.
+#ifndef TB_COUNTER_STRIDE_WORDS
+#define TB_COUNTER_STRIDE_WORDS 64
+#endif
+constexpr int kCounterStrideWords = TB_COUNTER_STRIDE_WORDS;
 
 // Workspace layout (byte offsets), fixed by B*Hq so that all operations agree on it:
-//   [0, cnt_bytes)             uint32 arrival counters, one per (b,h)      -- zero between calls
+//   [0, hist_off)              uint32 arrival counters, one per (b,h), 256 B apart -- zero between calls
 //   [hist_off, part_off)       uint32 level-1 histograms [B*Hq][2048]      -- zero between calls
 //   [part_off, ...)            fp32 split-attention partials [B*Hq][nsplit][D+2]
 struct WsLayout {

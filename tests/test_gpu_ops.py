@@ -55,7 +55,10 @@ def test_project_keys(oracle, dtype, D, Dimp, N, Hw):
     else:
         g64, r64 = oracle.bf16_to_f64(got[:, :, :N]), oracle.bf16_to_f64(ref)
         ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(r64), 2.0 ** -126))) - 7)
-        assert np.all(np.abs(g64 - r64) <= ulp * 1.0000001)
+        mag = np.einsum("bhnd,hdj->bhnj", np.abs(oracle.bf16_to_f64(np_of(K)[:, :, :N])),
+                        np.abs(np.broadcast_to(oracle.bf16_to_f64(np_of(W)), (Hkv,) + W.shape[1:])))
+        # one unit in the last place of the stored value plus the fp32-accumulation error of the sum
+        assert np.all(np.abs(g64 - r64) <= ulp * 1.0000001 + 1e-6 * mag)
         assert np.mean(got[:, :, :N] == ref) > 0.99  # and nearly always the same bits
 
 
