@@ -83,10 +83,13 @@ __device__ inline void store_elt(bf16_t* p, float v) { p->bits = f32_to_bf16_rne
 // NaN ranks with -inf and -0 equals +0 (selection policy).  The smallest key a real score can
 // produce is 0x007FFFFF (-inf), so key 0 is free to mark "not a candidate".
 __device__ inline uint32_t score_key(float s) {
-  uint32_t b = __float_as_uint(s);
-  if ((b & 0x7FFFFFFFu) > 0x7F800000u) b = 0xFF800000u;
-  if (b == 0x80000000u) b = 0u;
-  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+  const uint32_t b = __float_as_uint(s);
+  // flip all bits of negatives, only the sign bit of non-negatives
+  uint32_t key = b ^ (static_cast<uint32_t>(static_cast<int32_t>(b) >> 31) | 0x80000000u);
+  key = key < 0x007FFFFFu ? 0x007FFFFFu : key;    // negative NaN -> -inf
+  key = key > 0xFF800000u ? 0x007FFFFFu : key;    // positive NaN -> -inf
+  key += (key == 0x7FFFFFFFu) ? 1u : 0u;          // -0 -> +0
+  return key;
 }
 
 // Radix levels of the selection: 11 + 11 + 10 bits, most significant first.
@@ -98,7 +101,7 @@ constexpr int kBins3 = 1024;
 
 __device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }
 
-// Inclusive prefix sum across the 64 lanes of a wave.
+// Inclusive prefix sum across the 64 lanes of a wave (generic: LDS-crossbar shuffles).
 template <typename T>
 __device__ inline T wave_incl_scan(T v) {
   const int lane = lane_id();
@@ -108,6 +111,27 @@ __device__ inline T wave_incl_scan(T v) {
     if (lane >= off) v += o;
   }
   return v;
+}
+
+// 32-bit inclusive prefix sum with DPP moves (stays in the VALU, no LDS traffic): shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of row 0/2 is broadcast into row
+// 1/3 and the last lane of the lower half into the upper half.  Lanes whose source falls
+// outside the row (or outside the enabled rows) receive 0.
+__device__ inline uint32_t wave_incl_scan_u32(uint32_t v) {
+  constexpr int kRowShr = 0x110, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+  v += __builtin_amdgcn_update_dpp(0u, v, kRowShr + 1, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, kRowShr + 2, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, kRowShr + 4, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, kRowShr + 8, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, kRowBcast15, 0xA, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, kRowBcast31, 0xC, 0xF, false);
+  return v;
+}
+
+// Number of set bits of a wave-wide ballot in the lanes below this one.
+__device__ inline uint32_t lanes_below(unsigned long long ballot) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(ballot >> 32),
+                                   __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(ballot), 0u));
 }
 
 template <typename T>
@@ -139,6 +163,27 @@ __device__ inline T block_excl_scan(T v, T* s_tmp, T& total) {
   __syncthreads();
   const T base = s_tmp[wave];
   total = s_tmp[NWAVES];
+  __syncthreads();
+  return base + incl - v;
+}
+
+// Same for 32-bit counts, with the DPP wave scan; every thread adds up the totals of the
+// waves before its own (NWAVES <= 16 broadcast reads) instead of waiting for one thread.
+template <int NWAVES>
+__device__ inline uint32_t block_excl_scan_u32(uint32_t v, uint32_t* s_tmp, uint32_t& total) {
+  const int lane = lane_id();
+  const int wave = threadIdx.x / kWave;
+  const uint32_t incl = wave_incl_scan_u32(v);
+  if (lane == kWave - 1) s_tmp[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < NWAVES; ++w) {
+    const uint32_t t = s_tmp[w];
+    base += (w < wave) ? t : 0u;
+    all += t;
+  }
+  total = all;
   __syncthreads();
   return base + incl - v;
 }
