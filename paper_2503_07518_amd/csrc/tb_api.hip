@@ -15,6 +15,7 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
   if (max_rows <= 0 || units <= 0) {
     p.rows_per_wg = tile_rows_per_wg;
     p.nsplit = 1;
+    p.max_split = 1;
     return p;
   }
   const int64_t target_wgs = TB_ATTN_TARGET_WGS;
@@ -26,6 +27,7 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
   rows = (rows + tile_rows_per_wg - 1) / tile_rows_per_wg * tile_rows_per_wg;
   p.rows_per_wg = static_cast<int>(rows);
   p.nsplit = static_cast<int>((max_rows + rows - 1) / rows);
+  p.max_split = static_cast<int>(want);
   return p;
 }
 
@@ -263,7 +265,9 @@ size_t tb_workspace_bytes(int32_t op, const tb_cache_desc* d, int64_t max_count)
   if (op == TB_OP_SELECT) return ws_layout(units, d->D, 0).part_off;
   if (op == TB_OP_ATTN || op == TB_OP_DECODE_STEP) {
     const AttnPlan plan = attn_plan(units, max_count, attn_tile_rows_per_wg(d->dtype, d->D));
-    return ws_layout(units, d->D, plan.nsplit).total;
+    // sized for the largest split count a shorter list could get, so that one workspace serves
+    // every call whose list is no longer than max_count
+    return ws_layout(units, d->D, plan.max_split).total;
   }
   return 0;
 }

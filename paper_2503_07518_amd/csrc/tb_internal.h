@@ -30,6 +30,7 @@ struct WsLayout {
 struct AttnPlan {
   int rows_per_wg;  // list entries handled by one workgroup
   int nsplit;       // workgroups per (b,h)
+  int max_split;    // upper bound of nsplit for any list no longer than the one planned for
 };
 
 AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg);

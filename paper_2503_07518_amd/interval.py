@@ -1,0 +1,62 @@
+"""Prediction interval with neighbour fetching (Sec. 3.4), as a harness-level loop over the
+C-ABI entry points.  No arithmetic happens here: every step of the path is a library call.
+
+Step t sees the first ``N0 + t`` rows of the cache.  On prediction steps (``t % P == 0``) the
+newly appended keys are projected, the whole cache is scored, the top-k selection is made and
+attention runs on it; the selection widened by its neighbours is kept.  On the other steps
+attention runs on the kept list plus the dense tail of rows appended since the prediction (the
+local window is refreshed every step), and nothing else is touched.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as tb
+
+
+class IntervalDecoder:
+    def __init__(self, K, V, W, Kimp, Hq: int, k: int, P: int, radius: int, sink: int = 0, window: int = 0,
+                 sm_scale: float = 1.0, score_scale: float = 1.0, mode: int = 0, expand_on_predict: bool = False):
+        self.K, self.V, self.W, self.Kimp = K, V, W, Kimp
+        self.B, self.Hkv, self.Ncap, self.D = K.shape
+        self.Hq, self.k, self.P, self.radius = Hq, k, P, radius
+        self.sink, self.window, self.sm_scale, self.score_scale = sink, window, sm_scale, score_scale
+        self.mode, self.expand_on_predict = mode, expand_on_predict
+        dev = K.device
+        B = self.B
+        self.sel_cap = sink + k + window
+        mult = (2 * radius + 1) if mode == 0 else 2
+        self.exp_cap = min(self.Ncap, mult * self.sel_cap)
+        self.scores = torch.empty((B, Hq, (self.Ncap + 3) // 4 * 4), dtype=torch.float32, device=dev)
+        self.idx = torch.zeros((B, Hq, self.sel_cap), dtype=torch.int32, device=dev)
+        self.cnt = torch.zeros((B, Hq), dtype=torch.int32, device=dev)
+        self.exp_idx = torch.zeros((B, Hq, self.exp_cap), dtype=torch.int32, device=dev)
+        self.exp_cnt = torch.zeros((B, Hq), dtype=torch.int32, device=dev)
+        self.out = torch.empty((B, Hq, self.D), dtype=torch.float32, device=dev)
+        self.lse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
+        desc = tb.make_desc(self.Ncap, Hq, K=K, V=V, Kimp=Kimp)
+        self.ws = tb.new_workspace(tb.TB_OP_DECODE_STEP, desc, self.exp_cap + P)
+        self.N_pred = None
+        self.projected_upto = None
+
+    def step(self, t: int, N_t: int, q: torch.Tensor, q_imp: torch.Tensor):
+        """Returns (out, lse) views valid until the next call."""
+        desc = tb.make_desc(N_t, self.Hq, K=self.K, V=self.V, Kimp=self.Kimp)
+        if t % self.P == 0:
+            if self.projected_upto is None:
+                self.projected_upto = N_t  # the caller projected the post-prefill cache
+            if self.projected_upto < N_t:  # batched deferred projection of the rows appended since
+                tb.tb_project_keys(desc, self.K, self.W, self.Kimp, self.projected_upto, N_t)
+                self.projected_upto = N_t
+            tb.tb_decode_step(desc, q_imp, self.Kimp, self.score_scale, q, self.K, self.V, self.k, self.sink,
+                              self.window, self.sm_scale, self.scores, self.idx, self.cnt, self.out, self.lse, self.ws)
+            tb.tb_expand_neighbors(self.B, self.Hq, N_t, self.radius, self.mode, self.idx, self.cnt, self.exp_idx,
+                                   self.exp_cnt)
+            self.N_pred = N_t
+            if self.expand_on_predict:
+                tb.tb_sparse_decode_attn(desc, q, self.K, self.V, self.exp_idx, self.exp_cnt, self.exp_cap,
+                                         self.sm_scale, self.out, self.lse, self.ws)
+        else:
+            tb.tb_sparse_decode_attn(desc, q, self.K, self.V, self.exp_idx, self.exp_cnt, self.exp_cap,
+                                     self.sm_scale, self.out, self.lse, self.ws, tail_begin=self.N_pred, tail_end=N_t)
+        return self.out, self.lse
