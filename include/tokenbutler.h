@@ -78,7 +78,8 @@ tb_status tb_score(const tb_cache_desc* desc, const void* q_imp, const void* Kim
  * -inf, -0 equals +0, equal scores -> lower index first.  Output per (b,h), ascending:
  *   idx = [0,lo) ++ ascending(kept) ++ [hi,N),   count = lo + kk + (N - hi).
  * idx: int32 [B][Hq][idx_cap], idx_cap >= lo + kk + (N - hi); entries beyond count are left
- * untouched.  count: int32 [B][Hq].  ws: see tb_workspace_bytes(TB_OP_SELECT, ...). */
+ * untouched.  count: int32 [B][Hq].  The selection keeps its scratch on chip: ws / ws_bytes are
+ * accepted for symmetry and ignored (NULL / 0 is fine). */
 tb_status tb_select_topk(const tb_cache_desc* desc, const float* scores, int64_t score_stride, int32_t k,
                          int32_t sink, int32_t window, int32_t* idx, int32_t* count, int64_t idx_cap, void* ws,
                          size_t ws_bytes, void* stream);
@@ -112,8 +113,8 @@ tb_status tb_sparse_decode_attn(const tb_cache_desc* desc, const void* q, const 
                                 void* ws, size_t ws_bytes, void* stream);
 
 /* One prediction step in a single enqueue: tb_score -> tb_select_topk -> tb_sparse_decode_attn
- * with the first selection pass folded into the scoring kernel.  Results (scores, idx, count,
- * out, lse) are identical to calling the three entry points one after the other.
+ * with one validation pass and one launch plan.  Results (scores, idx, count, out, lse) are
+ * identical to calling the three entry points one after the other.
  * ws: tb_workspace_bytes(TB_OP_DECODE_STEP, ...). */
 tb_status tb_decode_step(const tb_cache_desc* desc, const void* q_imp, const void* Kimp, float score_scale,
                          const void* q, const void* K, const void* V, int32_t k, int32_t sink, int32_t window,
@@ -121,7 +122,7 @@ tb_status tb_decode_step(const tb_cache_desc* desc, const void* q_imp, const voi
                          int64_t idx_cap, float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /* Scratch size in bytes for `op` on this cache shape.  max_count is the longest list the
- * attention will see, tail included (ignored for TB_OP_SELECT; for TB_OP_DECODE_STEP it is
+ * attention will see, tail included (TB_OP_SELECT needs none: 0; for TB_OP_DECODE_STEP it is
  * the list length the selection policy produces, lo + kk + N - hi).  Returns 0 on invalid
  * input.  A workspace of the TB_OP_DECODE_STEP size serves all three operations on that
  * shape.  The workspace pointer must be 16-byte aligned. */

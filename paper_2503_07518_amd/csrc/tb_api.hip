@@ -33,8 +33,7 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
 
 WsLayout ws_layout(int64_t units, int D, int nsplit) {
   WsLayout w;
-  w.hist_off = align_up(static_cast<size_t>(units) * kCounterStrideWords * sizeof(uint32_t), 256);
-  w.part_off = w.hist_off + align_up(static_cast<size_t>(units) * kHistBinsHost * sizeof(uint32_t), 256);
+  w.part_off = align_up(static_cast<size_t>(units) * kCounterStrideWords * sizeof(uint32_t), 256);
   w.total = w.part_off + align_up(static_cast<size_t>(units) * nsplit * (D + 2) * sizeof(float), 256);
   return w;
 }
@@ -151,7 +150,7 @@ tb_status tb_score(const tb_cache_desc* d, const void* q_imp, const void* Kimp, 
                    int64_t score_stride, void* stream) {
   TB_TRY(check_score_args(d, q_imp, Kimp, scores, score_stride));
   if (d->B == 0 || d->Hq == 0) return TB_OK;
-  ScoreLaunch L{d, q_imp, Kimp, scale, scores, score_stride, nullptr, 0, 0};
+  ScoreLaunch L{d, q_imp, Kimp, scale, scores, score_stride};
   return launch_score(L, static_cast<hipStream_t>(stream));
 }
 
@@ -161,8 +160,8 @@ tb_status tb_select_topk(const tb_cache_desc* d, const float* scores, int64_t sc
   TB_TRY(check_select_args(d, scores, score_stride, k, sink, window, idx, count, idx_cap));
   const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
   if (units == 0) return TB_OK;
-  const WsLayout w = ws_layout(units, d->D, 0);
-  if (!ws || !aligned16(ws) || ws_bytes < w.part_off) return TB_ERR_WORKSPACE;
+  (void)ws;  // the selection keeps all of its scratch in LDS
+  (void)ws_bytes;
   const Policy p = policy(d->N, k, sink, window);
   SelectLaunch L;
   L.units = units;
@@ -175,8 +174,6 @@ tb_status tb_select_topk(const tb_cache_desc* d, const float* scores, int64_t sc
   L.idx = idx;
   L.count = count;
   L.idx_cap = idx_cap;
-  L.hist = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + w.hist_off);
-  L.hist_ready = false;
   return launch_select(L, static_cast<hipStream_t>(stream));
 }
 
@@ -229,11 +226,7 @@ tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* 
   const WsLayout w = ws_layout(units, d->D, plan.nsplit);
   if (!ws || !aligned16(ws) || ws_bytes < w.total) return TB_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  uint32_t* hist = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + w.hist_off);
-  const bool need_hist = p.kk > 0 && p.kk < p.hi - p.lo;
-
-  ScoreLaunch S{d, q_imp, Kimp, score_scale, scores, score_stride, need_hist ? hist : nullptr,
-                static_cast<int32_t>(p.lo), static_cast<int32_t>(p.hi)};
+  ScoreLaunch S{d, q_imp, Kimp, score_scale, scores, score_stride};
   TB_TRY(launch_score(S, st));
 
   SelectLaunch L;
@@ -247,8 +240,6 @@ tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* 
   L.idx = idx;
   L.count = count;
   L.idx_cap = idx_cap;
-  L.hist = hist;
-  L.hist_ready = true;
   TB_TRY(launch_select(L, st));
 
   AttnLaunch A{d,   q,   K,   V,
@@ -262,7 +253,7 @@ tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* 
 size_t tb_workspace_bytes(int32_t op, const tb_cache_desc* d, int64_t max_count) {
   if (check_desc(d) != TB_OK || max_count < 0) return 0;
   const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
-  if (op == TB_OP_SELECT) return ws_layout(units, d->D, 0).part_off;
+  if (op == TB_OP_SELECT) return 0;  // the selection needs no global scratch
   if (op == TB_OP_ATTN || op == TB_OP_DECODE_STEP) {
     const AttnPlan plan = attn_plan(units, max_count, attn_tile_rows_per_wg(d->dtype, d->D));
     // sized for the largest split count a shorter list could get, so that one workspace serves

@@ -10,7 +10,6 @@
 
 namespace tb {
 
-constexpr int kHistBinsHost = 2048;  // level-1 histogram bins per (b,h) kept in the workspace
 constexpr int64_t kSelectMaxN = 1 << 20;
 // Arrival counters sit 256 bytes apart so that the device-scope atomics of different heads do
 // not queue up on one cache line / memory channel.
@@ -20,11 +19,10 @@ constexpr int64_t kSelectMaxN = 1 << 20;
 constexpr int kCounterStrideWords = TB_COUNTER_STRIDE_WORDS;
 
 // Workspace layout (byte offsets), fixed by B*Hq so that all operations agree on it:
-//   [0, hist_off)              uint32 arrival counters, one per (b,h), 256 B apart -- zero between calls
-//   [hist_off, part_off)       uint32 level-1 histograms [B*Hq][2048]      -- zero between calls
+//   [0, part_off)              uint32 arrival counters, one per (b,h), 256 B apart -- zero between calls
 //   [part_off, ...)            fp32 split-attention partials [B*Hq][nsplit][D+2]
 struct WsLayout {
-  size_t hist_off, part_off, total;
+  size_t part_off, total;
 };
 
 struct AttnPlan {
@@ -45,8 +43,6 @@ struct ScoreLaunch {
   float scale;
   float* scores;
   int64_t score_stride;
-  uint32_t* hist;  // nullptr: no histogram
-  int32_t lo, hi;  // candidate range for the histogram
 };
 tb_status launch_score(const ScoreLaunch& a, hipStream_t st);
 
@@ -59,8 +55,6 @@ struct SelectLaunch {
   int32_t* idx;
   int32_t* count;
   int64_t idx_cap;
-  uint32_t* hist;
-  bool hist_ready;  // level-1 histogram already accumulated by the scoring kernel
 };
 tb_status launch_select(const SelectLaunch& a, hipStream_t st);
 

@@ -4,42 +4,42 @@
 // bytes (64 B for the Llama-shaped configs); LPR = row_bytes/16 adjacent lanes each take one
 // 128-bit load of a row, so a wave instruction reads 1 KiB of consecutive memory.  Every
 // loaded row is used for all g query heads of its KV head (the cache is read once per KV
-// head).  Each thread issues all of its loads before consuming any of them.
-//
-// Optionally the kernel also accumulates the first radix level of the selection: a per-head
-// histogram of the top 11 bits of the order-preserving score key, built in LDS per workgroup
-// and flushed with one global atomic per non-empty bin.
+// head).  Each thread issues all of its loads before consuming any of them; workgroups are
+// small (256 threads) so that several of them overlap on a compute unit and the memory
+// pipeline never drains between them.
 #include "tb_device.h"
 #include "tb_internal.h"
 
 namespace tb {
 namespace {
 
-constexpr int kScoreThreads = 1024;
-constexpr int kLoadsPerThread = 4;
+#ifndef TB_SCORE_THREADS
+#define TB_SCORE_THREADS 256
+#endif
+#ifndef TB_SCORE_LOADS
+#define TB_SCORE_LOADS 4
+#endif
+constexpr int kScoreThreads = TB_SCORE_THREADS;
+constexpr int kLoadsPerThread = TB_SCORE_LOADS;
 
 struct ScoreArgs {
   const void* q_imp;
   const void* Kimp;
   float* scores;
-  uint32_t* hist;
   int64_t N;
   int64_t ki_stride_b, ki_stride_h, ki_stride_n;
   int64_t score_stride;
   int32_t Hq;
-  int32_t lo, hi;
   float scale;
 };
 
-template <typename T, int DIMP, int G, bool HIST>
+template <typename T, int DIMP, int G>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   constexpr int EPL = Pack16<T>::kElts;      // elements per lane (one 128-bit load)
   constexpr int LPR = DIMP / EPL;            // lanes per projected row
   constexpr int RPP = kScoreThreads / LPR;   // rows per pass of the workgroup
   constexpr int RW = RPP * kLoadsPerThread;  // rows per workgroup
   static_assert(LPR >= 1 && LPR <= 16 && (LPR & (LPR - 1)) == 0, "row must span 1..16 lanes");
-
-  __shared__ uint32_t s_hist[HIST ? G * kBins1 : 1];
 
   const int tid = threadIdx.x;
   const int part = tid % LPR;
@@ -48,23 +48,15 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   const int hkv = blockIdx.y;
   const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RW;
 
-  if (HIST) {
-    for (int i = tid; i < G * kBins1; i += kScoreThreads) s_hist[i] = 0;
-  }
-
   const T* kbase = static_cast<const T*>(a.Kimp) + b * a.ki_stride_b + hkv * a.ki_stride_h + part * EPL;
 
-  // issue every load of this thread first
-  float kv[kLoadsPerThread][EPL];
+  // issue every load of this thread first (kept packed until used)
+  typename Pack16<T>::Raw kraw[kLoadsPerThread];
 #pragma unroll
   for (int i = 0; i < kLoadsPerThread; ++i) {
-    const int64_t row = row0 + i * RPP + rsub;
-    if (row < a.N) {
-      Pack16<T>::load(kbase + row * a.ki_stride_n, kv[i]);
-    } else {
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) kv[i][e] = 0.f;
-    }
+    int64_t row = row0 + i * RPP + rsub;
+    row = row < a.N ? row : a.N - 1;  // clamp: the result of a clamped row is not stored
+    kraw[i] = Pack16<T>::load_raw(kbase + row * a.ki_stride_n);
   }
 
   // this lane's slice of the g importance queries
@@ -73,18 +65,18 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
 #pragma unroll
   for (int hh = 0; hh < G; ++hh) Pack16<T>::load(qbase + hh * DIMP, qv[hh]);
 
-  if (HIST) __syncthreads();
-
   float* sbase = a.scores + (static_cast<int64_t>(b) * a.Hq + hkv * G) * a.score_stride;
 #pragma unroll
   for (int i = 0; i < kLoadsPerThread; ++i) {
     const int64_t row = row0 + i * RPP + rsub;
+    float kf[EPL];
+    Pack16<T>::unpack(kraw[i], kf);
     float acc[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
       float s = 0.f;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) s = fmaf(qv[hh][e], kv[i][e], s);
+      for (int e = 0; e < EPL; ++e) s = fmaf(qv[hh][e], kf[e], s);
 #pragma unroll
       for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off, kWave);
       acc[hh] = s * a.scale;
@@ -92,20 +84,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     if (row < a.N) {
 #pragma unroll
       for (int hh = 0; hh < G; ++hh) {
-        if ((hh % LPR) == part) {
-          sbase[hh * a.score_stride + row] = acc[hh];
-          if (HIST && row >= a.lo && row < a.hi) atomicAdd(&s_hist[hh * kBins1 + (score_key(acc[hh]) >> kShift1)], 1u);
-        }
+        if ((hh % LPR) == part) sbase[hh * a.score_stride + row] = acc[hh];
       }
-    }
-  }
-
-  if (HIST) {
-    __syncthreads();
-    uint32_t* gh = a.hist + (static_cast<int64_t>(b) * a.Hq + hkv * G) * kBins1;
-    for (int i = tid; i < G * kBins1; i += kScoreThreads) {
-      const uint32_t c = s_hist[i];
-      if (c) atomicAdd(&gh[i], c);
     }
   }
 }
@@ -119,22 +99,16 @@ tb_status launch_tdg(const ScoreLaunch& L, hipStream_t st) {
   a.q_imp = L.q_imp;
   a.Kimp = L.Kimp;
   a.scores = L.scores;
-  a.hist = L.hist;
   a.N = d.N;
   a.ki_stride_b = d.ki_stride_b;
   a.ki_stride_h = d.ki_stride_h;
   a.ki_stride_n = d.ki_stride_n;
   a.score_stride = L.score_stride;
   a.Hq = d.Hq;
-  a.lo = L.lo;
-  a.hi = L.hi;
   a.scale = L.scale;
   if (d.N == 0) return TB_OK;
   dim3 grid(static_cast<unsigned>((d.N + RW - 1) / RW), d.Hkv, d.B);
-  if (L.hist)
-    hipLaunchKernelGGL((score_kernel<T, DIMP, G, true>), grid, dim3(kScoreThreads), 0, st, a);
-  else
-    hipLaunchKernelGGL((score_kernel<T, DIMP, G, false>), grid, dim3(kScoreThreads), 0, st, a);
+  hipLaunchKernelGGL((score_kernel<T, DIMP, G>), grid, dim3(kScoreThreads), 0, st, a);
   return hip_status(hipGetLastError());
 }
 

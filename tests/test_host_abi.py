@@ -64,7 +64,7 @@ def test_workspace_sizes(tb):
     sel = tb.tb_workspace_bytes(tb.TB_OP_SELECT, d, 0)
     att = tb.tb_workspace_bytes(tb.TB_OP_ATTN, d, 500)
     step = tb.tb_workspace_bytes(tb.TB_OP_DECODE_STEP, d, 500)
-    assert sel >= 8 * 2048 * 4 and att >= sel and step == att
+    assert sel == 0 and att >= 8 * 256 and step == att
     assert tb.tb_workspace_bytes(99, d, 0) == 0
     assert tb.tb_workspace_bytes(tb.TB_OP_ATTN, desc(tb, D=96), 10) == 0
     assert tb.tb_workspace_bytes(tb.TB_OP_ATTN, d, -1) == 0
@@ -97,8 +97,6 @@ def test_rejects_bad_arguments_without_launching(tb):
     # selection: negative budget, capacity too small, missing workspace, N too large
     assert L.tb_select_topk(r(d), P, 1000, -1, 0, 0, P, P, 100, P, 1 << 20, None) == tb.TB_ERR_INVALID_ARG
     assert L.tb_select_topk(r(d), P, 1000, 10, 4, 4, P, P, 17, P, 1 << 20, None) == tb.TB_ERR_INVALID_ARG
-    assert L.tb_select_topk(r(d), P, 1000, 10, 4, 4, P, P, 18, NULL, 0, None) == tb.TB_ERR_WORKSPACE
-    assert L.tb_select_topk(r(d), P, 1000, 10, 4, 4, P, P, 18, P, 16, None) == tb.TB_ERR_WORKSPACE
     big = desc(tb, N=(1 << 20) + 4)
     assert L.tb_select_topk(r(big), P, (1 << 20) + 4, 10, 0, 0, P, P, 10, P, 1 << 20, None) == tb.TB_ERR_UNSUPPORTED
     # neighbours: output capacity, mode, aliasing
