@@ -312,12 +312,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     for (int c = 0; c < 4; ++c) cnt += (k4[c] > T ? 1u : 0u) + ((k4[c] == T && T) ? 0x10000u : 0u);
     return cnt;
   };
-  uint32_t pre[NT > 0 ? NT : 1];
+  constexpr bool kKeepPre = NT > 0 && NT <= 8;  // keep the in-tile prefixes when registers allow
+  uint32_t pre[kKeepPre ? NT : 1];
   uint32_t run_gt = 0, run_eq = 0;
   for_each_tile([&](int j, const uint32_t(&k4)[4]) {
     const uint32_t cnt = tile_count(k4);
     const uint32_t incl = wave_incl_scan_u32(cnt);
-    if (NT > 0) pre[NT > 0 ? j : 0] = incl - cnt;
+    if (kKeepPre) pre[kKeepPre ? j : 0] = incl - cnt;
     const uint32_t tot = __builtin_amdgcn_readlane(incl, kWave - 1);
     run_gt += tot & 0xFFFFu;
     run_eq += tot >> 16;
@@ -340,8 +341,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   for_each_tile([&](int j, const uint32_t(&k4)[4]) {
     const uint32_t cnt = tile_count(k4);
     uint32_t excl;
-    if (NT > 0) {
-      excl = pre[NT > 0 ? j : 0];
+    if (kKeepPre) {
+      excl = pre[kKeepPre ? j : 0];
     } else {
       excl = wave_incl_scan_u32(cnt) - cnt;
     }
@@ -404,7 +405,9 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
     hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, st, a);
   else if (tiles <= 8)
     hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, st, a);
-  else  // more than 32 keys per thread do not fit the register file without spilling
+  else if (tiles <= 16)
+    hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, st, a);
+  else
     hipLaunchKernelGGL(select_kernel<0>, grid, block, 0, st, a);
   return hip_status(hipGetLastError());
 }
