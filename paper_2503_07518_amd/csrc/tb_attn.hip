@@ -152,8 +152,7 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
       float s = 0.f;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kf[e], s);
-#pragma unroll
-      for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off, kWave);
+      s = group_allreduce_sum<LPR>(s);
       sc[t] = valid[t] ? s : -INFINITY;
       tmax = fmaxf(tmax, sc[t]);
     }

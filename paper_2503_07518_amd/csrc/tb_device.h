@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace tb {
 
 constexpr int kWave = 64;
@@ -132,6 +134,26 @@ __device__ inline uint32_t wave_incl_scan_u32(uint32_t v) {
 __device__ inline uint32_t lanes_below(unsigned long long ballot) {
   return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(ballot >> 32),
                                    __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(ballot), 0u));
+}
+
+// Sum over aligned groups of LANES adjacent lanes (LANES = 1..32, a power of two); every lane
+// of a group receives the group's total.  The exchanges inside a row of 16 lanes are DPP moves
+// (swap neighbours, swap pairs, mirror the half row, mirror the row) and stay in the VALU;
+// only a 32-lane group needs one cross-row shuffle.
+template <int LANES>
+__device__ inline float group_allreduce_sum(float s) {
+  constexpr int kQuadSwap1 = 0xB1;  // quad_perm [1,0,3,2]
+  constexpr int kQuadSwap2 = 0x4E;  // quad_perm [2,3,0,1]
+  constexpr int kRowHalfMirror = 0x141, kRowMirror = 0x140;
+  auto dpp = [](float x, auto ctrl) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, 0xF, 0xF, false));
+  };
+  if (LANES >= 2) s += dpp(s, std::integral_constant<int, kQuadSwap1>{});
+  if (LANES >= 4) s += dpp(s, std::integral_constant<int, kQuadSwap2>{});
+  if (LANES >= 8) s += dpp(s, std::integral_constant<int, kRowHalfMirror>{});
+  if (LANES >= 16) s += dpp(s, std::integral_constant<int, kRowMirror>{});
+  if (LANES >= 32) s += __shfl_xor(s, 16, kWave);
+  return s;
 }
 
 template <typename T>

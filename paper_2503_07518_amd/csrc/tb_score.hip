@@ -65,27 +65,33 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
 #pragma unroll
   for (int hh = 0; hh < G; ++hh) Pack16<T>::load(qbase + hh * DIMP, qv[hh]);
 
-  float* sbase = a.scores + (static_cast<int64_t>(b) * a.Hq + hkv * G) * a.score_stride;
+  // scores of the workgroup's RW rows for the g heads, staged in LDS so that they leave as
+  // full 128-bit stores (1 KiB per wave instruction) instead of 64-byte pieces
+  __shared__ float s_out[G][RW];
 #pragma unroll
   for (int i = 0; i < kLoadsPerThread; ++i) {
-    const int64_t row = row0 + i * RPP + rsub;
     float kf[EPL];
     Pack16<T>::unpack(kraw[i], kf);
-    float acc[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
       float s = 0.f;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) s = fmaf(qv[hh][e], kf[e], s);
-#pragma unroll
-      for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off, kWave);
-      acc[hh] = s * a.scale;
+      s = group_allreduce_sum<LPR>(s) * a.scale;
+      if ((hh % LPR) == part) s_out[hh][i * RPP + rsub] = s;
     }
-    if (row < a.N) {
-#pragma unroll
-      for (int hh = 0; hh < G; ++hh) {
-        if ((hh % LPR) == part) sbase[hh * a.score_stride + row] = acc[hh];
-      }
+  }
+  __syncthreads();
+  float* sbase = a.scores + (static_cast<int64_t>(b) * a.Hq + hkv * G) * a.score_stride + row0;
+  constexpr int V4 = RW / 4;  // float4 groups per head
+  for (int v = tid; v < G * V4; v += kScoreThreads) {
+    const int hh = v / V4, r4 = (v % V4) * 4;
+    float* dst = sbase + hh * a.score_stride + r4;
+    if (row0 + r4 + 3 < a.N) {
+      *reinterpret_cast<float4*>(dst) = *reinterpret_cast<const float4*>(&s_out[hh][r4]);
+    } else {
+      for (int c = 0; c < 4; ++c)
+        if (row0 + r4 + c < a.N) dst[c] = s_out[hh][r4 + c];
     }
   }
 }
