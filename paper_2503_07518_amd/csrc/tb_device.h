@@ -94,13 +94,6 @@ __device__ inline uint32_t score_key(float s) {
   return key;
 }
 
-// Radix levels of the selection: 11 + 11 + 10 bits, most significant first.
-constexpr int kBins1 = 2048;
-constexpr int kShift1 = 21;
-constexpr int kBins2 = 2048;
-constexpr int kShift2 = 10;
-constexpr int kBins3 = 1024;
-
 __device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }
 
 // Inclusive prefix sum across the 64 lanes of a wave (generic: LDS-crossbar shuffles).

@@ -244,6 +244,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     }
     int cur = 1;  // s_hist[cur] is clear and becomes this level's histogram
     bool dense_level = true;
+    bool take_whole_bin = false;
 #pragma nounroll
     for (int call = 1; call <= kMaxLevels; ++call) {
       uint32_t* h = s_hist[cur];
@@ -281,6 +282,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         lo_key += s_found[call][0] << shift;
         need = want - s_found[call][1];
         if (shift == 0) break;
+        if (need == h[s_found[call][0]]) {
+          // every key of this sub-bin is needed: no reason to look at its low bits
+          take_whole_bin = true;
+          break;
+        }
         const int nshift = shift > 12 ? shift - 12 : 0;
         nbins = 1u << (shift - nshift);
         span = 1u << shift;
@@ -300,6 +306,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     TB_MARK(3);
     T = lo_key;
     r_eq = need;
+    if (take_whole_bin) {  // keep everything from the start of the sub-bin upwards
+      T = lo_key - 1u;
+      r_eq = 0u;
+    }
     TB_MARK(4);
   }
   // kk == hi - lo: T = 0 keeps every candidate (all real keys are > 0)
