@@ -35,6 +35,10 @@ def randn(shape, dtype, seed, scale=1.0):
     (torch.bfloat16, 64, 64, 129, 1),
     (torch.float32, 128, 64, 65, 3),
     (torch.bfloat16, 128, 16, 1, 1),
+    # enough rows for the matrix-core form (bf16, Dimp 32), ragged last tile
+    (torch.bfloat16, 128, 32, 4133, 1),
+    (torch.bfloat16, 64, 32, 2501, 3),
+    (torch.bfloat16, 128, 32, 2048, 3),
 ])
 def test_project_keys(oracle, dtype, D, Dimp, N, Hw):
     say(f"project dtype={dtype} D={D} Dimp={Dimp} N={N} Hw={Hw}")
@@ -62,17 +66,18 @@ def test_project_keys(oracle, dtype, D, Dimp, N, Hw):
         assert np.mean(got[:, :, :N] == ref) > 0.99  # and nearly always the same bits
 
 
-def test_project_identity_and_row_range(oracle):
-    say("project identity W, row range")
-    B, Hkv, N, D, Dimp = 1, 2, 500, 128, 32
+@pytest.mark.parametrize("N,n_begin,n_end", [(500, 70, 391), (5000, 70, 4391)])
+def test_project_identity_and_row_range(oracle, N, n_begin, n_end):
+    say(f"project identity W, row range [{n_begin}, {n_end}) of {N}")
+    B, Hkv, D, Dimp = 1, 2, 128, 32
     K = randn((B, Hkv, N, D), torch.bfloat16, 3)
     W = torch.zeros((1, D, Dimp), dtype=torch.bfloat16, device=DEV)
-    W[0, :Dimp, :] = torch.eye(Dimp, dtype=torch.bfloat16)
+    W[0, 3:3 + Dimp, :] = torch.eye(Dimp, dtype=torch.bfloat16)
     Kimp = torch.full((B, Hkv, N, Dimp), 7.0, dtype=torch.bfloat16, device=DEV)
-    gpu_project(K, W, N, n_begin=70, n_end=391, Kimp=Kimp)
+    gpu_project(K, W, N, n_begin=n_begin, n_end=n_end, Kimp=Kimp)
     torch.cuda.synchronize()
-    assert torch.equal(Kimp[:, :, 70:391], K[:, :, 70:391, :Dimp])
-    assert torch.all(Kimp[:, :, :70] == 7.0) and torch.all(Kimp[:, :, 391:] == 7.0)
+    assert torch.equal(Kimp[:, :, n_begin:n_end], K[:, :, n_begin:n_end, 3:3 + Dimp])
+    assert torch.all(Kimp[:, :, :n_begin] == 7.0) and torch.all(Kimp[:, :, n_end:] == 7.0)
 
 
 def test_project_strided_cache(oracle):
