@@ -65,6 +65,9 @@ class LayerBuffers:
         self.out = torch.empty((B, Hq, D), dtype=torch.float32, device="cuda")
         self.lse = torch.empty((B, Hq), dtype=torch.float32, device="cuda")
         self.ws = tb.new_workspace(tb.TB_OP_DECODE_STEP, self.desc, self.need)
+        # target of the timed batched projection (the cache that the step reads stays as it is)
+        self.Kimp_bulk = torch.empty_like(self.Kimp)
+        self.desc_bulk = tb.make_desc(N, Hq, K=self.K, V=self.V, Kimp=self.Kimp_bulk)
 
     def nbytes(self):
         return sum(t.numel() * t.element_size() for t in (self.K, self.V, self.Kimp, self.scores, self.idx))
@@ -107,6 +110,9 @@ def main():
 
     def stage_project_append(b):
         tb.tb_project_keys(b.desc, b.K, b.W, b.Kimp, cfg.N - 1, cfg.N)
+
+    def stage_project_bulk(b):
+        tb.tb_project_keys(b.desc_bulk, b.K, b.W, b.Kimp_bulk, 0, cfg.N)
 
     # a plain device copy of known size: the reference dispatch that HBM byte counters of a
     # profiler run are scaled by (256 MiB read + 256 MiB written)
@@ -178,6 +184,7 @@ def main():
     us_select = timer(stage_select)
     us_attn = timer(stage_attn)
     us_proj = timer(stage_project_append)
+    us_proj_bulk = timer(stage_project_bulk)
     us_step_eager = time_eager(step, args.steps, args.warmup) if use_graph else us_step
 
     elt = cfg.elt_bytes
@@ -185,6 +192,8 @@ def main():
     bytes_gather = selected_rows * 2 * cfg.D * elt
     bytes_step = bytes_kimp + bytes_gather
     step_gbps = bytes_step / us_step / 1e3
+    bytes_proj_bulk = cfg.B * cfg.Hkv * cfg.N * (cfg.D + cfg.Dimp) * elt
+    proj_gbps = bytes_proj_bulk / us_proj_bulk / 1e3
     attn_gbps = bytes_gather / us_attn / 1e3
 
     result = {
@@ -212,6 +221,13 @@ def main():
         "stages_us": {
             "score": round(us_score, 3), "select_topk": round(us_select, 3), "sparse_attn": round(us_attn, 3),
             "project_append_1row": round(us_proj, 3), "step_eager_launch": round(us_step_eager, 3),
+        },
+        # the batched projection of the whole key cache (done once per window of appended tokens,
+        # not per step): read K, write K_imp
+        "project_bulk": {
+            "us": round(us_proj_bulk, 3), "algorithmic_bytes": bytes_proj_bulk, "achieved": round(proj_gbps, 1),
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(proj_gbps / HBM_PEAK_GBPS, 4),
+            "tflops": round(2.0 * cfg.B * cfg.Hkv * cfg.N * cfg.D * cfg.Dimp / us_proj_bulk / 1e6, 1),
         },
         "roofline": {
             "kernel": "attn_kernel (tb_sparse_decode_attn)", "bound": "hbm", "achieved": round(attn_gbps, 1),

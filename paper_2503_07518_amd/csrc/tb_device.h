@@ -85,13 +85,11 @@ __device__ inline void store_elt(bf16_t* p, float v) { p->bits = f32_to_bf16_rne
 // NaN ranks with -inf and -0 equals +0 (selection policy).  The smallest key a real score can
 // produce is 0x007FFFFF (-inf), so key 0 is free to mark "not a candidate".
 __device__ inline uint32_t score_key(float s) {
-  const uint32_t b = __float_as_uint(s);
+  // IEEE maxNum returns the operand that is a number, so NaN becomes -inf; adding +0 turns -0
+  // into +0 and changes nothing else (subnormals are kept: fp32 denormal mode is "preserve")
+  const uint32_t b = __float_as_uint(fmaxf(s, -__builtin_inff()) + 0.0f);
   // flip all bits of negatives, only the sign bit of non-negatives
-  uint32_t key = b ^ (static_cast<uint32_t>(static_cast<int32_t>(b) >> 31) | 0x80000000u);
-  key = key < 0x007FFFFFu ? 0x007FFFFFu : key;    // negative NaN -> -inf
-  key = key > 0xFF800000u ? 0x007FFFFFu : key;    // positive NaN -> -inf
-  key += (key == 0x7FFFFFFFu) ? 1u : 0u;          // -0 -> +0
-  return key;
+  return b ^ (static_cast<uint32_t>(static_cast<int32_t>(b) >> 31) | 0x80000000u);
 }
 
 __device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }

@@ -42,7 +42,6 @@ constexpr int kWaveTile = kWave * 4;              // scores per wave tile: one f
 constexpr int kTileElts = kSelWaves * kWaveTile;  // scores per workgroup-wide tile (4096)
 constexpr int kHistBins = 4096;                   // LDS histogram size (12 bits per level)
 constexpr int kTopShift = 20;                     // key >> 20 = top 12 bits
-constexpr int kPerThread = kHistBins / kSelThreads;
 
 struct SelectArgs {
   const float* scores;
@@ -82,59 +81,95 @@ __device__ inline void load_keys4(const float* s, int64_t N, int lo, int hi, int
   }
 }
 
-// Walk an LDS histogram of `nbins` (<= 4096) bins from the highest bin down and report, for
-// each of two targets need_a <= need_b, the bin in which the running count reaches it and the
-// count in strictly higher bins.  A target beyond the total (or 0) reports nothing and leaves
-// the preset {0, 0}.  Results in s_found[0..1] (a) and s_found[2..3] (b); returns the total.
-// Two barriers; s_scan (16 words) and s_found (4 words, preset to 0) are per call site.
-__device__ inline uint32_t find_bins(const uint32_t* s_hist, int nbins, uint32_t need_a, uint32_t need_b,
-                                     uint32_t* s_scan, uint32_t* s_found) {
-  const int tid = threadIdx.x;
-  const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
-  uint32_t v[kPerThread];
-  uint32_t sum = 0;
-#pragma unroll
-  for (int i = 0; i < kPerThread; ++i) {
-    const int bin = nbins - 1 - (kPerThread * tid + i);  // thread t owns 4 consecutive bins, descending
-    v[i] = bin >= 0 ? s_hist[bin] : 0u;
-    sum += v[i];
-  }
-  const uint32_t incl = wave_incl_scan_u32(sum);
-  if (lane == kWave - 1) s_scan[wave] = incl;
-  __syncthreads();
-  uint32_t run = incl - sum, total = 0;
-#pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
-    const uint32_t t = s_scan[w];
-    run += (w < wave) ? t : 0u;
-    total += t;
-  }
-#pragma unroll
-  for (int i = 0; i < kPerThread; ++i) {
-    const uint32_t bin = static_cast<uint32_t>(nbins - 1 - (kPerThread * tid + i));
-    if (run < need_a && need_a <= run + v[i]) {
-      s_found[0] = bin;
-      s_found[1] = run;
-    }
-    if (run < need_b && need_b <= run + v[i]) {
-      s_found[2] = bin;
-      s_found[3] = run;
-    }
-    run += v[i];
-  }
-  __syncthreads();
-  return total;
+// The 16 per-wave values in s_w (complete after a barrier): returns the sum of the entries of
+// the waves before this one and, in `total`, the sum of all.  Every wave scans the 16 values in
+// one DPP row (lane i of each row holds entry i) instead of adding up 16 LDS reads per thread.
+__device__ inline uint32_t wave_entries_scan(const uint32_t* s_w, uint32_t& total) {
+  static_assert(kSelWaves == 16, "one DPP row holds the per-wave entries");
+  constexpr int kRowShr = 0x110;
+  const uint32_t v = s_w[threadIdx.x & (kSelWaves - 1)];
+  uint32_t incl = v;
+  incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 1, 0xF, 0xF, false);
+  incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 2, 0xF, 0xF, false);
+  incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 4, 0xF, 0xF, false);
+  incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 8, 0xF, 0xF, false);
+  total = __builtin_amdgcn_readlane(incl, kSelWaves - 1);
+  return __builtin_amdgcn_readlane(incl - v, threadIdx.x / kWave);
 }
 
-__device__ inline uint32_t block_sum_u32(uint32_t v, uint32_t* s_part) {
-  const uint32_t incl = wave_incl_scan_u32(v);
-  if (lane_id() == kWave - 1) s_part[threadIdx.x / kWave] = incl;
-  __syncthreads();
-  uint32_t total = 0;
+// Result of a histogram walk, published in LDS for the whole workgroup.
+struct Found {
+  uint32_t bin_a, above_a;  // bin in which the running count (from the top bin down) reaches target a, count above it
+  uint32_t bin_b, above_b;  // same for target b
+  uint32_t extra_total;     // block-wide sum of `extra`
+  uint32_t total;           // sum of all bins
+  uint32_t need_a, need_b;  // the targets that were searched
+};
+static_assert(sizeof(Found) == 32, "two 128-bit LDS reads");
+
+// Walk the 4096-entry LDS histogram (entries the caller does not use are 0) from the highest
+// bin down and find, for each of two targets, the bin in which the running count reaches it
+// and the count in strictly higher bins.  A target of 0 or beyond the total finds nothing and
+// leaves the preset {0, 0}.  The targets may depend on a second block-wide sum: every wave
+// reduces `extra`, and `targets(extra_total, need_a, need_b)` turns the total into the targets.
+//
+// The walk itself is done by wave 0 alone (the other 15 waves would only repeat it: on one
+// compute unit a workgroup-wide instruction costs 16 issue slots): lane l sums the 64 bins
+// [64*(63-l), 64*(63-l)+63] with 128-bit reads in a rotated order (conflict-free), a wave scan
+// finds the lane whose chunk contains the target, and the 64 lanes then scan that chunk.
+// Two barriers: the first completes the histogram that the callers fill with LDS atomics.
+// s_extra (16 words) and s_found (preset to 0) are per call site.
+template <typename Targets>
+__device__ inline Found find_bins(const uint32_t* s_hist, uint32_t extra, uint32_t* s_extra, Found* s_found,
+                                  Targets&& targets) {
+  const int lane = lane_id();
+  const int wave = threadIdx.x / kWave;
+  const uint32_t extra_incl = wave_incl_scan_u32(extra);
+  if (lane == kWave - 1) s_extra[wave] = extra_incl;
+  __syncthreads();  // the histogram and s_extra are complete
+  if (wave == 0) {
+    const int chunk = (kWave - 1 - lane) * 64;
+    uint32_t sum = 0;
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) total += s_part[w];
-  return total;
+    for (int i = 0; i < 16; ++i) {
+      const uint4 q = *reinterpret_cast<const uint4*>(s_hist + chunk + ((i + lane) & 15) * 4);
+      sum += (q.x + q.y) + (q.z + q.w);
+    }
+    const uint32_t incl = wave_incl_scan_u32(sum);
+    const uint32_t before = incl - sum;
+    uint32_t extra_total;
+    wave_entries_scan(s_extra, extra_total);
+    uint32_t need[2];
+    targets(extra_total, need[0], need[1]);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const unsigned long long hit = __ballot(before < need[t] && need[t] <= incl);
+      if (hit) {  // at most one lane: the chunk that contains the target
+        const int L = __ffsll(hit) - 1;
+        const uint32_t base = __builtin_amdgcn_readlane(before, L);
+        const uint32_t bin = static_cast<uint32_t>((kWave - 1 - L) * 64 + (kWave - 1 - lane));
+        const uint32_t v = s_hist[bin];
+        const uint32_t run = base + wave_incl_scan_u32(v) - v;
+        if (run < need[t] && need[t] <= run + v) {
+          if (t == 0) {
+            s_found->bin_a = bin;
+            s_found->above_a = run;
+          } else {
+            s_found->bin_b = bin;
+            s_found->above_b = run;
+          }
+        }
+      }
+    }
+    if (lane == 0) {
+      s_found->extra_total = extra_total;
+      s_found->total = __builtin_amdgcn_readlane(incl, kWave - 1);
+      s_found->need_a = need[0];
+      s_found->need_b = need[1];
+    }
+  }
+  __syncthreads();
+  return *s_found;
 }
 
 constexpr int kMaxLevels = 4;  // bracketed level (possibly repeated once over all bins) + up to 2 levels of low bits
@@ -143,8 +178,7 @@ template <int NT>  // NT > 0: the wave's tiles are cached in registers (NT >= ti
                    // NT == 0: streamed again in every phase
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   __shared__ uint32_t s_hist[2][kHistBins];  // alternating: one in use, the other being cleared
-  __shared__ uint32_t s_scan[kMaxLevels + 2][kSelWaves];
-  __shared__ uint32_t s_found[kMaxLevels + 1][4];
+  __shared__ __attribute__((aligned(16))) Found s_found[kMaxLevels + 1];
   __shared__ uint32_t s_part[2][kSelWaves];
   __shared__ uint32_t s_wgt[kSelWaves], s_weq[kSelWaves];
 
@@ -166,7 +200,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     for (int j = 0; j < NT; ++j) load_keys4(s, a.N, lo, hi, wbase + j * kWaveTile, keys[j]);
   }
   for (int i = tid; i < 2 * kHistBins; i += kSelThreads) (&s_hist[0][0])[i] = 0;
-  if (tid < (kMaxLevels + 1) * 4) (&s_found[0][0])[tid] = 0;
+  if (tid < (kMaxLevels + 1) * 8) reinterpret_cast<uint32_t*>(s_found)[tid] = 0;
 
   // always-kept ranges: sink prefix [0, lo) and local window [hi, N)
   for (int64_t n = tid; n < lo; n += kSelThreads) out[n] = static_cast<int32_t>(n);
@@ -211,18 +245,18 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         ++n_valid;
       }
     }
-    const uint32_t n_s = block_sum_u32(n_valid, s_part[0]);  // barrier inside: the sample histogram is complete
     // rank of the threshold inside the sample and its spread (binomial), in fp32: a heuristic
     // only -- the exact counts of level 1 decide whether the bracket holds
-    const float frac = static_cast<float>(kk) / static_cast<float>(hi - lo);
-    const float ks_f = frac * static_cast<float>(n_s);
-    const float margin = 6.0f * sqrtf(ks_f * (1.0f - frac)) + 4.0f;
-    const float hi_f = ks_f - margin, lo_f = ks_f + margin;
-    const uint32_t need_hi = hi_f < 1.0f ? 0u : static_cast<uint32_t>(hi_f);  // 0: no bin is safely above T
-    const uint32_t need_lo = lo_f >= static_cast<float>(n_s) ? n_s + 1u : static_cast<uint32_t>(lo_f) + 1u;
-    find_bins(s_hist[0], kHistBins, need_hi, need_lo, s_scan[0], s_found[0]);
-    uint32_t b_hi = need_hi ? s_found[0][0] : (kHistBins - 1);  // top bin of the bracket
-    uint32_t b_lo = (need_lo <= n_s) ? s_found[0][2] : 1u;      // bottom bin of the bracket
+    const Found fb = find_bins(s_hist[0], n_valid, s_part[0], &s_found[0], [&](uint32_t n_s, uint32_t& na, uint32_t& nb) {
+      const float frac = static_cast<float>(kk) / static_cast<float>(hi - lo);
+      const float ks_f = frac * static_cast<float>(n_s);
+      const float margin = 6.0f * sqrtf(ks_f * (1.0f - frac)) + 4.0f;
+      const float hi_f = ks_f - margin, lo_f = ks_f + margin;
+      na = hi_f < 1.0f ? 0u : static_cast<uint32_t>(hi_f);  // 0: no bin is safely above T
+      nb = lo_f >= static_cast<float>(n_s) ? n_s + 1u : static_cast<uint32_t>(lo_f) + 1u;
+    });
+    uint32_t b_hi = fb.need_a ? fb.bin_a : (kHistBins - 1);            // top bin of the bracket
+    uint32_t b_lo = (fb.need_b <= fb.extra_total) ? fb.bin_b : 1u;     // bottom bin of the bracket
     if (b_lo < 1u) b_lo = 1u;                                   // bin 0 holds only "not a candidate"
     if (b_hi < b_lo) b_hi = b_lo;
     TB_MARK(2);
@@ -263,26 +297,31 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
       } else {
         // only the handful of keys of one sub-bin take part: skip wave-uniformly
         for_each_tile([&](int, const uint32_t(&k4)[4]) {
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const uint32_t d = k4[c] - lo_key;
-            if (__any(d < span)) {
-              if (d < span) atomicAdd(&h[d >> shift], 1u);
-            }
+          const uint32_t d0 = k4[0] - lo_key, d1 = k4[1] - lo_key, d2 = k4[2] - lo_key, d3 = k4[3] - lo_key;
+          const uint32_t dmin = min(min(d0, d1), min(d2, d3));
+          if (__any(dmin < span)) {
+            if (d0 < span) atomicAdd(&h[d0 >> shift], 1u);
+            if (d1 < span) atomicAdd(&h[d1 >> shift], 1u);
+            if (d2 < span) atomicAdd(&h[d2 >> shift], 1u);
+            if (d3 < span) atomicAdd(&h[d3 >> shift], 1u);
           }
         });
       }
+      TB_MARK(8 + 4 * call);
       // clear the other histogram for the next level while this one is being filled
       for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[cur ^ 1][i] = 0;
-      const uint32_t c_above = block_sum_u32(n_above, s_part[call & 1]);  // barrier inside
-      const uint32_t want = (c_above < need) ? need - c_above : 0u;
-      const uint32_t total_in = find_bins(h, static_cast<int>(nbins), want, want, s_scan[call], s_found[call]);
+      const Found f = find_bins(h, n_above, s_part[call & 1], &s_found[call], [&](uint32_t c_above, uint32_t& na, uint32_t& nb) {
+        na = (c_above < need) ? need - c_above : 0u;
+        nb = 0u;
+      });
+      const uint32_t want = f.need_a, total_in = f.total;
+      TB_MARK(10 + 4 * call);
       cur ^= 1;
       if (want >= 1u && want <= total_in) {  // T lies inside this level's range: descend
-        lo_key += s_found[call][0] << shift;
-        need = want - s_found[call][1];
+        lo_key += f.bin_a << shift;
+        need = want - f.above_a;
         if (shift == 0) break;
-        if (need == h[s_found[call][0]]) {
+        if (need == h[f.bin_a]) {
           // every key of this sub-bin is needed: no reason to look at its low bits
           take_whole_bin = true;
           break;
@@ -339,12 +378,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   }
   __syncthreads();
   TB_MARK(5);
-  uint32_t base_gt = 0, base_eq = 0;  // kept / tied keys in the spans of the waves before this one
-#pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
-    base_gt += (w < wave) ? s_wgt[w] : 0u;
-    base_eq += (w < wave) ? s_weq[w] : 0u;
-  }
+  // kept / tied keys in the spans of the waves before this one
+  uint32_t unused_total;
+  uint32_t base_gt = wave_entries_scan(s_wgt, unused_total);
+  uint32_t base_eq = wave_entries_scan(s_weq, unused_total);
 
   // Pass B: position of a kept key = (#greater before it) + min(#equal before it, r_eq)
   int32_t* sel_out = out + lo;
