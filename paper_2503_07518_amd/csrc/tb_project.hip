@@ -1,10 +1,11 @@
 // Key-cache projection K_imp = K W: rows [n_begin, n_end) of every (b, kv-head).
 //
-// One workgroup projects a tile of 64 cache rows.  W (D x Dimp) and the K tile are staged in
-// LDS as fp32, 64 columns of the head dimension per round; thread (row, quarter) accumulates
-// Dimp/4 adjacent outputs in fp32 and rounds once (round to nearest even) to the storage type.
-// The same kernel serves the one-row append of a decode step and the batched projection of a
-// window of rows.
+// Two forms.  project_kernel serves every shape, the one-row append of a decode step included:
+// a workgroup projects a tile of 64 cache rows, W (D x Dimp) and the K tile are staged in LDS as
+// fp32, 64 columns of the head dimension per round; thread (row, quarter) accumulates Dimp/4
+// adjacent outputs in fp32 and rounds once (round to nearest even) to the storage type.
+// project_mfma_kernel is the batched form for bf16 with Dimp = 32 (a window of appended rows,
+// or the whole cache after prefill) on the matrix cores.
 #include "tb_device.h"
 #include "tb_internal.h"
 
