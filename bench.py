@@ -73,6 +73,72 @@ class LayerBuffers:
         return sum(t.numel() * t.element_size() for t in (self.K, self.V, self.Kimp, self.scores, self.idx))
 
 
+def time_interval_loop(cfg, tb, workloads, torch, replays=5):
+    """The prediction-interval loop of the config (cfg.steps decode steps, a prediction every
+    cfg.P steps, neighbours of radius cfg.radius on the steps in between) as one HIP graph:
+    mean time per step, and the rows that attention gathers on the two kinds of step."""
+    from paper_2503_07518_amd import interval
+
+    data = workloads.make_layer(cfg, layer=1, seed=0, device="cuda")
+    K, V, W = data["K"], data["V"], data["W"]
+    Kimp = torch.zeros((cfg.B, cfg.Hkv, K.shape[2], cfg.Dimp), dtype=K.dtype, device="cuda")
+    tb.tb_project_keys(tb.make_desc(cfg.N, cfg.Hq, K=K, V=V, Kimp=Kimp), K, W, Kimp, 0, cfg.N)
+    qs = [data["q"][t].contiguous() for t in range(cfg.steps)]
+    qis = [data["q_imp"][t].contiguous() for t in range(cfg.steps)]
+
+    dec = interval.IntervalDecoder(K, V, W, Kimp, cfg.Hq, cfg.k, cfg.P, cfg.radius, sink=cfg.sink,
+                                   window=cfg.window, sm_scale=cfg.sm_scale)
+
+    def loop():
+        dec.N_pred = dec.projected_upto = None  # the cache is back at its post-prefill length
+        for t in range(cfg.steps):
+            dec.step(t, cfg.N + t, qs[t], qis[t])
+
+    loop()  # eager once: first touch, and the list sizes for the byte counts
+    torch.cuda.synchronize()
+    sel_rows = int(dec.cnt.sum().item())
+    exp_rows = int(dec.exp_cnt.sum().item())
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            loop()
+    torch.cuda.current_stream().wait_stream(side)
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    cur = torch.cuda.current_stream()
+    e0.record(cur)
+    for _ in range(replays):
+        g.replay()
+    e1.record(cur)
+    torch.cuda.synchronize()
+    us_loop = e0.elapsed_time(e1) * 1e3 / replays
+    n_pred = -(-cfg.steps // cfg.P)
+    # one reuse step on its own (attention over the widened list + the rows appended since)
+    t_last = cfg.steps - 1
+    N_last = cfg.N + t_last
+    desc = tb.make_desc(N_last, cfg.Hq, K=K, V=V, Kimp=Kimp)
+    e0.record(cur)
+    for _ in range(20):
+        tb.tb_sparse_decode_attn(desc, qs[t_last], K, V, dec.exp_idx, dec.exp_cnt, dec.exp_cap, cfg.sm_scale, dec.out,
+                                 dec.lse, dec.ws, tail_begin=dec.N_pred, tail_end=N_last)
+    e1.record(cur)
+    torch.cuda.synchronize()
+    us_reuse = e0.elapsed_time(e1) * 1e3 / 20
+    reuse_bytes = (exp_rows + cfg.B * cfg.Hq * (N_last - dec.N_pred)) * 2 * cfg.D * cfg.elt_bytes
+    return {
+        "steps": cfg.steps, "P": cfg.P, "radius": cfg.radius, "prediction_steps": n_pred,
+        "reuse_steps": cfg.steps - n_pred, "us_per_step_mean": round(us_loop / cfg.steps, 3),
+        "us_loop": round(us_loop, 1),
+        "rows_gathered_last_prediction_step": sel_rows, "rows_in_widened_list": exp_rows,
+        "reuse_step": {"us": round(us_reuse, 3), "algorithmic_bytes": reuse_bytes,
+                       "achieved": round(reuse_bytes / us_reuse / 1e3, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                       "frac": round(reuse_bytes / us_reuse / 1e3 / HBM_PEAK_GBPS, 4)},
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -237,6 +303,9 @@ def main():
         },
         "timed_wall_s": round(wall_s, 3),
     }
+
+    if cfg.P > 1:
+        result["interval_loop"] = time_interval_loop(cfg, tb, workloads, torch)
 
     if not args.no_cpu_baseline:
         import numpy as np
