@@ -54,21 +54,19 @@ struct SelectArgs {
   int32_t tiles_per_wave;
 };
 
-// Keys of the four consecutive positions n0 .. n0+3 (n0 a multiple of 4).  Positions outside
-// the candidate range get key 0 (no real score has a key below 0x007FFFFF).
-__device__ inline void load_keys4(const float* s, int64_t N, int lo, int hi, int64_t n0, uint32_t (&key)[4]) {
-  float v[4] = {0.f, 0.f, 0.f, 0.f};
-  if (n0 + 3 < N) {
-    const float4 f = *reinterpret_cast<const float4*>(s + n0);
-    v[0] = f.x;
-    v[1] = f.y;
-    v[2] = f.z;
-    v[3] = f.w;
-  } else {
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-      if (n0 + c < N) v[c] = s[n0 + c];
-  }
+// The four scores at positions n0 .. n0+3 (n0 a multiple of 4) as one 128-bit load without any
+// branch, so that a thread's loads can all be in flight together.  A row's allocation covers
+// score_stride >= N entries and score_stride is a multiple of 4, so the vector that holds the
+// last score lies inside it; a position past that vector (`last4`) is clamped to it, and
+// keys_of4 -- which gets the unclamped position -- masks what was read.
+__device__ inline float4 load_scores4(const float* s, int64_t last4, int64_t n0) {
+  return *reinterpret_cast<const float4*>(s + (n0 < last4 ? n0 : last4));
+}
+
+// Keys of the positions n0 .. n0+3.  Positions outside the candidate range [lo, hi) get key 0
+// (no real score has a key below 0x007FFFFF).
+__device__ inline void keys_of4(const float4& f, int lo, int hi, int64_t n0, uint32_t (&key)[4]) {
+  const float v[4] = {f.x, f.y, f.z, f.w};
   if (n0 >= lo && n0 + 3 < hi) {  // the usual case: all four are candidates
 #pragma unroll
     for (int c = 0; c < 4; ++c) key[c] = score_key(v[c]);
@@ -172,6 +170,11 @@ __device__ inline Found find_bins(const uint32_t* s_hist, uint32_t extra, uint32
   return *s_found;
 }
 
+// Streamed rows (NT == 0) keep the keys that fall inside the bracket in LDS, so that only two
+// passes read the scores: the bracketed level and the final write-out.
+constexpr int kListCap = 16384;
+constexpr int kStreamBatch = 8;  // tiles in flight per wave while streaming
+
 constexpr int kMaxLevels = 4;  // bracketed level (possibly repeated once over all bins) + up to 2 levels of low bits
 
 template <int NT>  // NT > 0: the wave's tiles are cached in registers (NT >= tiles per wave);
@@ -181,6 +184,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   __shared__ __attribute__((aligned(16))) Found s_found[kMaxLevels + 1];
   __shared__ uint32_t s_part[2][kSelWaves];
   __shared__ uint32_t s_wgt[kSelWaves], s_weq[kSelWaves];
+  // streamed rows only: keys inside the bracket (with the wave whose span they come from), the
+  // number appended (the list is unusable when it exceeds the capacity), every wave's count of
+  // keys above the bracket, and per-(counting wave, owning wave) tallies of kept / tied keys
+  constexpr bool kStream = NT == 0;
+  __shared__ uint32_t s_ckey[kStream ? kListCap : 1];
+  __shared__ uint8_t s_cwave[kStream ? kListCap : 4];
+  __shared__ uint32_t s_nlist;
+  __shared__ uint32_t s_wabove[kSelWaves];
+  __shared__ uint32_t s_lcnt[kStream ? kSelWaves : 1][kSelWaves][2];
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
@@ -194,13 +206,19 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   const bool refine = kk > 0 && kk < hi - lo;
 
   TB_MARK(0);
+  const int64_t last4 = a.N > 0 ? ((a.N - 1) & ~int64_t{3}) : 0;  // the vector that holds the last score
   uint32_t keys[NT > 0 ? NT : 1][4];
   if (NT > 0 && kk > 0) {
+    float4 raw[NT > 0 ? NT : 1];  // every load of the thread is issued before the first is used
 #pragma unroll
-    for (int j = 0; j < NT; ++j) load_keys4(s, a.N, lo, hi, wbase + j * kWaveTile, keys[j]);
+    for (int j = 0; j < NT; ++j) raw[j] = load_scores4(s, last4, wbase + j * kWaveTile);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) keys_of4(raw[j], lo, hi, wbase + j * kWaveTile, keys[j]);
   }
   for (int i = tid; i < 2 * kHistBins; i += kSelThreads) (&s_hist[0][0])[i] = 0;
   if (tid < (kMaxLevels + 1) * 8) reinterpret_cast<uint32_t*>(s_found)[tid] = 0;
+  if (tid == 0) s_nlist = 0;
 
   // always-kept ranges: sink prefix [0, lo) and local window [hi, N)
   for (int64_t n = tid; n < lo; n += kSelThreads) out[n] = static_cast<int32_t>(n);
@@ -214,22 +232,41 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
 #pragma unroll
       for (int j = 0; j < NT; ++j) body(j, keys[j]);
     } else {
-      for (int j = 0; j < tpw; ++j) {
-        uint32_t k4[4];
-        load_keys4(s, a.N, lo, hi, wbase + static_cast<int64_t>(j) * kWaveTile, k4);
-        body(j, k4);
+      // streamed: the loads of kStreamBatch tiles are issued before the first tile is used (one
+      // load per iteration would leave a wave with 1 KiB in flight and the pass latency-bound)
+      for (int j0 = 0; j0 < tpw; j0 += kStreamBatch) {
+        float4 raw[kStreamBatch];
+#pragma unroll
+        for (int t = 0; t < kStreamBatch; ++t)  // tiles past the wave's span read a clamped address and are dropped
+          raw[t] = load_scores4(s, last4, wbase + static_cast<int64_t>(j0 + t) * kWaveTile);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < kStreamBatch; ++t) {
+          if (j0 + t < tpw) {
+            uint32_t k4[4];
+            keys_of4(raw[t], lo, hi, wbase + static_cast<int64_t>(j0 + t) * kWaveTile, k4);
+            body(j0 + t, k4);
+          }
+        }
       }
     }
   };
 
-  uint32_t T = 0;     // threshold key: everything above is kept
-  uint32_t r_eq = 0;  // how many keys equal to T are kept (lowest indices first)
+  uint32_t T = 0;        // threshold key: everything above is kept
+  uint32_t r_eq = 0;     // how many keys equal to T are kept (lowest indices first)
+  bool list_ok = false;  // streamed rows: the LDS list holds every key inside the bracket
   if (refine) {
     __syncthreads();  // LDS initialised
     TB_MARK(1);
     // ---- bracket from a sample: the first key of (up to) four tiles per thread
     constexpr int kSamples = (NT > 0 && NT < 4) ? NT : 4;
     uint32_t n_valid = 0;
+    float4 sraw[kSamples];
+    if constexpr (NT == 0) {
+#pragma unroll
+      for (int i = 0; i < kSamples; ++i)
+        sraw[i] = load_scores4(s, last4, wbase + static_cast<int64_t>((i * tpw) / kSamples) * kWaveTile);
+    }
 #pragma unroll
     for (int i = 0; i < kSamples; ++i) {
       uint32_t ks;
@@ -237,7 +274,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         ks = keys[(i * NT) / kSamples][0];
       } else {
         uint32_t k4[4];
-        load_keys4(s, a.N, lo, hi, wbase + static_cast<int64_t>((i * tpw) / kSamples) * kWaveTile, k4);
+        keys_of4(sraw[i], lo, hi, wbase + static_cast<int64_t>((i * tpw) / kSamples) * kWaveTile, k4);
         ks = k4[0];
       }
       if (ks) {
@@ -283,7 +320,39 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
     for (int call = 1; call <= kMaxLevels; ++call) {
       uint32_t* h = s_hist[cur];
       uint32_t n_above = 0;
-      if (dense_level) {
+      if (kStream && call == 1) {
+        // the bracketed level of a streamed row: as the dense level below, and the keys inside
+        // the bracket are appended to the LDS list (one slot reservation per wave tile)
+        for_each_tile([&](int, const uint32_t(&k4)[4]) {
+          uint32_t d[4], nin = 0;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            d[c] = k4[c] - lo_key;
+            n_above += (k4[c] > above_key) ? 1u : 0u;
+            if (d[c] < span) {
+              atomicAdd(&h[d[c] >> shift], 1u);
+              ++nin;
+            }
+          }
+          const uint32_t incl = wave_incl_scan_u32(nin);
+          const uint32_t tot = __builtin_amdgcn_readlane(incl, kWave - 1);
+          if (tot) {
+            uint32_t base = 0;
+            if (lane == kWave - 1) base = atomicAdd(&s_nlist, tot);
+            uint32_t pos = __builtin_amdgcn_readlane(base, kWave - 1) + incl - nin;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              if (d[c] < span) {
+                if (pos < static_cast<uint32_t>(kListCap)) {
+                  s_ckey[kStream ? pos : 0] = k4[c];
+                  s_cwave[kStream ? pos : 0] = static_cast<uint8_t>(wave);
+                }
+                ++pos;
+              }
+            }
+          }
+        });
+      } else if (dense_level) {
         // a sizeable share of the keys falls into the range: test every key on its own.
         // (key > above_key implies key - lo_key >= span, so the two cases are disjoint.)
         for_each_tile([&](int, const uint32_t(&k4)[4]) {
@@ -294,6 +363,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
             if (d < span) atomicAdd(&h[d >> shift], 1u);
           }
         });
+      } else if (list_ok) {
+        // streamed row: the keys of the chosen sub-bin are all in the LDS list
+        const uint32_t nl = s_nlist;
+        for (uint32_t i = tid; i < nl; i += kSelThreads) {
+          const uint32_t d = s_ckey[kStream ? i : 0] - lo_key;
+          if (d < span) atomicAdd(&h[d >> shift], 1u);
+        }
       } else {
         // only the handful of keys of one sub-bin take part: skip wave-uniformly
         for_each_tile([&](int, const uint32_t(&k4)[4]) {
@@ -315,6 +391,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         nb = 0u;
       });
       const uint32_t want = f.need_a, total_in = f.total;
+      if (kStream && call == 1) {
+        list_ok = s_nlist <= static_cast<uint32_t>(kListCap);
+        if (tid < kSelWaves) s_wabove[tid] = s_part[1][tid];  // per-wave counts of keys above the bracket
+      }
       TB_MARK(10 + 4 * call);
       cur ^= 1;
       if (want >= 1u && want <= total_in) {  // T lies inside this level's range: descend
@@ -340,6 +420,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
         shift = kTopShift;
         nbins = kHistBins - 1;
         above_key = 0xFFFFFFFFu;
+        list_ok = false;
       }
     }
     TB_MARK(3);
@@ -363,18 +444,45 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
   };
   constexpr bool kKeepPre = NT > 0 && NT <= 8;  // keep the in-tile prefixes when registers allow
   uint32_t pre[kKeepPre ? NT : 1];
-  uint32_t run_gt = 0, run_eq = 0;
-  for_each_tile([&](int j, const uint32_t(&k4)[4]) {
-    const uint32_t cnt = tile_count(k4);
-    const uint32_t incl = wave_incl_scan_u32(cnt);
-    if (kKeepPre) pre[kKeepPre ? j : 0] = incl - cnt;
-    const uint32_t tot = __builtin_amdgcn_readlane(incl, kWave - 1);
-    run_gt += tot & 0xFFFFu;
-    run_eq += tot >> 16;
-  });
-  if (lane == 0) {
-    s_wgt[wave] = run_gt;
-    s_weq[wave] = run_eq;
+  if (list_ok) {
+    // streamed row: the per-wave totals come from the list instead of another pass over the
+    // scores (a key above the bracket is kept for sure; a key below it never is)
+    for (int i = tid; i < (kStream ? kSelWaves : 1) * kSelWaves * 2; i += kSelThreads) (&s_lcnt[0][0][0])[i] = 0;
+    __syncthreads();
+    const uint32_t nl = s_nlist;
+    for (uint32_t i = tid; i < nl; i += kSelThreads) {
+      const uint32_t key = s_ckey[kStream ? i : 0];
+      const uint32_t w = s_cwave[kStream ? i : 0];
+      if (key > T) {
+        atomicAdd(&s_lcnt[kStream ? wave : 0][w][0], 1u);
+      } else if (key == T) {
+        atomicAdd(&s_lcnt[kStream ? wave : 0][w][1], 1u);
+      }
+    }
+    __syncthreads();
+    if (tid < kSelWaves) {
+      uint32_t gt = s_wabove[tid], eq = 0;
+      for (int cw = 0; cw < (kStream ? kSelWaves : 1); ++cw) {
+        gt += s_lcnt[cw][tid][0];
+        eq += s_lcnt[cw][tid][1];
+      }
+      s_wgt[tid] = gt;
+      s_weq[tid] = eq;
+    }
+  } else {
+    uint32_t run_gt = 0, run_eq = 0;
+    for_each_tile([&](int j, const uint32_t(&k4)[4]) {
+      const uint32_t cnt = tile_count(k4);
+      const uint32_t incl = wave_incl_scan_u32(cnt);
+      if (kKeepPre) pre[kKeepPre ? j : 0] = incl - cnt;
+      const uint32_t tot = __builtin_amdgcn_readlane(incl, kWave - 1);
+      run_gt += tot & 0xFFFFu;
+      run_eq += tot >> 16;
+    });
+    if (lane == 0) {
+      s_wgt[wave] = run_gt;
+      s_weq[wave] = run_eq;
+    }
   }
   __syncthreads();
   TB_MARK(5);

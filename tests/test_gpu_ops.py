@@ -151,6 +151,25 @@ def test_select_sizes_random_scores(oracle, N):
         check_select(oracle, scores, N, 0, 3, 4)
 
 
+@pytest.mark.parametrize("N,ks", [
+    (131072, (4096, 13000, 65536)),      # streamed rows: the bracket's keys fit the LDS list
+    (300001, (1, 4096, 30000, 150000)),  # ... and overflow it for the larger budgets
+    (1 << 20, (4096, 104857)),           # longest supported row
+])
+def test_select_streamed_rows(oracle, N, ks):
+    say(f"select streamed N={N}")
+    scores = randn((1, 2, (N + 3) // 4 * 4), torch.float32, 200 + N % 1000)
+    for k in ks:
+        check_select(oracle, scores, N, k, 0, 0)
+    check_select(oracle, scores, N, ks[0], 128, 256)
+    # heavy ties around the threshold and a sorted row (every candidate in one wave's span)
+    g = torch.Generator().manual_seed(N)
+    tied = torch.randint(0, 50, scores.shape, generator=g).to(torch.float32)
+    check_select(oracle, tied.to(DEV), N, ks[0], 0, 0)
+    asc = torch.arange(scores.shape[-1], dtype=torch.float32).view(1, 1, -1)
+    check_select(oracle, asc.to(DEV), N, ks[0], 0, 0)
+
+
 @pytest.mark.parametrize("N", [777, 9000, 66000])
 def test_select_ties_and_special_values(oracle, N):
     say(f"select ties/specials N={N}")
