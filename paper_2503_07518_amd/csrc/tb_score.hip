@@ -19,6 +19,7 @@ namespace {
 #ifndef TB_SCORE_LOADS
 #define TB_SCORE_LOADS 4
 #endif
+typedef uint32_t nt_u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kScoreThreads = TB_SCORE_THREADS;
 constexpr int kLoadsPerThread = TB_SCORE_LOADS;
 
@@ -56,7 +57,12 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
   for (int i = 0; i < kLoadsPerThread; ++i) {
     int64_t row = row0 + i * RPP + rsub;
     row = row < a.N ? row : a.N - 1;  // clamp: the result of a clamped row is not stored
-    kraw[i] = Pack16<T>::load_raw(kbase + row * a.ki_stride_n);
+    {
+      // the projected keys are streamed once per step: a non-temporal load keeps them from
+      // displacing the scores (which the selection reads next) in the caches
+      const nt_u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4*>(kbase + row * a.ki_stride_n));
+      __builtin_memcpy(&kraw[i], &t, 16);
+    }
   }
 
   // this lane's slice of the g importance queries

@@ -179,7 +179,7 @@ constexpr int kMaxLevels = 4;  // bracketed level (possibly repeated once over a
 
 template <int NT>  // NT > 0: the wave's tiles are cached in registers (NT >= tiles per wave);
                    // NT == 0: streamed again in every phase
-__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a) {
+__global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void select_kernel(SelectArgs a) {
   __shared__ uint32_t s_hist[2][kHistBins];  // alternating: one in use, the other being cleared
   __shared__ __attribute__((aligned(16))) Found s_found[kMaxLevels + 1];
   __shared__ uint32_t s_part[2][kSelWaves];
