@@ -40,6 +40,11 @@ def parse_args():
     ap.add_argument("--config", default="C2_llama3_8b_32k")
     ap.add_argument("--copies", type=int, default=0, help="rotating buffer copies (0: enough for >= 1 GiB)")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of replaying a HIP graph")
+    ap.add_argument("--kv-layout", choices=("separate", "interleaved"), default="separate",
+                    help="K and V as two arrays, or one array [B][Hkv][N][2][D] (a token's K and V rows adjacent)")
+    ap.add_argument("--kv-host", action="store_true",
+                    help="offloaded cache: K and V in pinned host memory, projected keys on the GPU; "
+                         "only the selected rows cross the host link")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
@@ -48,9 +53,12 @@ def parse_args():
 class LayerBuffers:
     """One copy of a layer's inputs and outputs in HBM."""
 
-    def __init__(self, cfg, seed, tb, workloads, torch):
+    def __init__(self, cfg, seed, tb, workloads, torch, kv_layout="separate", kv_host=False):
         data = workloads.make_layer(cfg, layer=0, seed=seed, device="cuda")
         self.K, self.V, self.W = data["K"], data["V"], data["W"]
+        if kv_layout == "interleaved":
+            kv = torch.stack((self.K, self.V), dim=3)  # [B][Hkv][N][2][D]
+            self.K, self.V = kv[:, :, :, 0, :], kv[:, :, :, 1, :]
         self.q = data["q"][0].contiguous()
         self.q_imp = data["q_imp"][0].contiguous()
         B, Hq, Hkv, N, D = cfg.B, cfg.Hq, cfg.Hkv, cfg.N, cfg.D
@@ -65,6 +73,11 @@ class LayerBuffers:
         self.out = torch.empty((B, Hq, D), dtype=torch.float32, device="cuda")
         self.lse = torch.empty((B, Hq), dtype=torch.float32, device="cuda")
         self.ws = tb.new_workspace(tb.TB_OP_DECODE_STEP, self.desc, self.need)
+        if kv_host:  # the projected keys are made; now the cache itself moves to pinned host memory
+            torch.cuda.synchronize()
+            self.K = torch.empty(self.K.shape, dtype=self.K.dtype, pin_memory=True).copy_(self.K)
+            self.V = torch.empty(self.V.shape, dtype=self.V.dtype, pin_memory=True).copy_(self.V)
+            self.desc = tb.make_desc(N, Hq, K=self.K, V=self.V, Kimp=self.Kimp)
         # target of the timed batched projection (the cache that the step reads stays as it is)
         self.Kimp_bulk = torch.empty_like(self.Kimp)
         self.desc_bulk = tb.make_desc(N, Hq, K=self.K, V=self.V, Kimp=self.Kimp_bulk)
@@ -153,12 +166,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     tb.load_library()
-    cfg = workloads.CONFIGS[args.config]
+    cfg = {**workloads.CONFIGS, **workloads.EXTRA_CONFIGS}[args.config]
 
     # ---- buffers: enough distinct copies that a step never finds its data in the last-level cache
-    probe = LayerBuffers(cfg, 0, tb, workloads, torch)
-    copies = args.copies or max(2, -(-(1 << 30) // probe.nbytes()))
-    bufs = [probe] + [LayerBuffers(cfg, s, tb, workloads, torch) for s in range(1, copies)]
+    probe = LayerBuffers(cfg, 0, tb, workloads, torch, args.kv_layout, args.kv_host)
+    copies = args.copies or (2 if args.kv_host else max(2, -(-(1 << 30) // probe.nbytes())))
+    bufs = [probe] + [LayerBuffers(cfg, s, tb, workloads, torch, args.kv_layout, args.kv_host)
+                      for s in range(1, copies)]
     torch.cuda.synchronize()
 
     def step(b):
@@ -250,7 +264,8 @@ def main():
     us_select = timer(stage_select)
     us_attn = timer(stage_attn)
     us_proj = timer(stage_project_append)
-    us_proj_bulk = timer(stage_project_bulk)
+    # (with the cache in host memory the batched projection would time the host link, not the kernel)
+    us_proj_bulk = timer(stage_project_bulk) if not args.kv_host else float("inf")
     us_step_eager = time_eager(step, args.steps, args.warmup) if use_graph else us_step
 
     elt = cfg.elt_bytes
@@ -278,7 +293,8 @@ def main():
         "config": {
             "workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "N": cfg.N,
             "d_imp": cfg.Dimp, "k": cfg.k, "sink": cfg.sink, "window": cfg.window,
-            "buffer_copies": copies, "launch": "hipgraph" if use_graph else "eager",
+            "buffer_copies": copies, "kv_layout": args.kv_layout,
+            "kv_memory": "pinned host" if args.kv_host else "hbm", "launch": "hipgraph" if use_graph else "eager",
         },
         "step_hbm": {
             "algorithmic_bytes": bytes_step, "achieved": round(step_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -304,6 +320,11 @@ def main():
         "timed_wall_s": round(wall_s, 3),
     }
 
+    if args.kv_host:
+        # the gathered rows cross the host link (PCIe 5.0 x16: 64 GB/s per direction); HBM is not the bound
+        result["roofline"].update({"bound": "host_link", "peak": 64.0, "frac": round(attn_gbps / 64.0, 4),
+                                   "traffic": None})
+        result.pop("project_bulk")
     if cfg.P > 1:
         result["interval_loop"] = time_interval_loop(cfg, tb, workloads, torch)
 

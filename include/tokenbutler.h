@@ -78,8 +78,11 @@ tb_status tb_score(const tb_cache_desc* desc, const void* q_imp, const void* Kim
  * -inf, -0 equals +0, equal scores -> lower index first.  Output per (b,h), ascending:
  *   idx = [0,lo) ++ ascending(kept) ++ [hi,N),   count = lo + kk + (N - hi).
  * idx: int32 [B][Hq][idx_cap], idx_cap >= lo + kk + (N - hi); entries beyond count are left
- * untouched.  count: int32 [B][Hq].  The selection keeps its scratch on chip: ws / ws_bytes are
- * accepted for symmetry and ignored (NULL / 0 is fine). */
+ * untouched.  count: int32 [B][Hq].  ws / ws_bytes are optional (NULL / 0 is fine): the selection
+ * keeps its scratch on chip, except that long rows on few heads (N >= 131072, B*Hq <= 128) are
+ * cut into pieces that are selected by several compute units and then combined, which needs
+ * tb_workspace_bytes(TB_OP_SELECT, desc, sink + k + window) bytes; with less, one workgroup
+ * selects the whole row (same result, slower). */
 tb_status tb_select_topk(const tb_cache_desc* desc, const float* scores, int64_t score_stride, int32_t k,
                          int32_t sink, int32_t window, int32_t* idx, int32_t* count, int64_t idx_cap, void* ws,
                          size_t ws_bytes, void* stream);
@@ -122,8 +125,9 @@ tb_status tb_decode_step(const tb_cache_desc* desc, const void* q_imp, const voi
                          int64_t idx_cap, float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /* Scratch size in bytes for `op` on this cache shape.  max_count is the longest list the
- * attention will see, tail included (TB_OP_SELECT needs none: 0; for TB_OP_DECODE_STEP it is
- * the list length the selection policy produces, lo + kk + N - hi).  Returns 0 on invalid
+ * attention will see, tail included; for TB_OP_SELECT and TB_OP_DECODE_STEP it is the list
+ * length the selection policy produces, lo + kk + N - hi (TB_OP_SELECT returns 0 for every
+ * shape whose rows are selected by one workgroup each).  Returns 0 on invalid
  * input.  A workspace of the TB_OP_DECODE_STEP size serves all three operations on that
  * shape.  The workspace pointer must be 16-byte aligned. */
 size_t tb_workspace_bytes(int32_t op, const tb_cache_desc* desc, int64_t max_count);

@@ -31,6 +31,25 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
   return p;
 }
 
+SelectPlan select_plan(int64_t units, int64_t N, int64_t kk) {
+  SelectPlan p{1, 0, 0};
+  if (units <= 0 || kk <= 0 || N < 131072) return p;
+  int64_t s = 256 / units;                      // pieces per head that the 256 compute units can take
+  if (s > N / 32768) s = N / 32768;             // a piece is worth a workgroup from 32K scores on
+  if (s > 16) s = 16;
+  if (s < 2) return p;
+  int64_t len = (N + s - 1) / s;
+  len = (len + 4095) / 4096 * 4096;
+  s = (N + len - 1) / len;
+  if (s < 2) return p;
+  const int64_t per_piece = kk < len ? kk : len;
+  if (s * per_piece > N / 2) return p;           // the second stage would be as long as the row
+  p.chunks = static_cast<int>(s);
+  p.chunk_len = len;
+  p.cand_stride = (s * per_piece + 3) / 4 * 4;
+  return p;
+}
+
 WsLayout ws_layout(int64_t units, int D, int nsplit) {
   WsLayout w;
   w.part_off = align_up(static_cast<size_t>(units) * kCounterStrideWords * sizeof(uint32_t), 256);
@@ -160,8 +179,6 @@ tb_status tb_select_topk(const tb_cache_desc* d, const float* scores, int64_t sc
   TB_TRY(check_select_args(d, scores, score_stride, k, sink, window, idx, count, idx_cap));
   const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
   if (units == 0) return TB_OK;
-  (void)ws;  // the selection keeps all of its scratch in LDS
-  (void)ws_bytes;
   const Policy p = policy(d->N, k, sink, window);
   SelectLaunch L;
   L.units = units;
@@ -174,6 +191,11 @@ tb_status tb_select_topk(const tb_cache_desc* d, const float* scores, int64_t sc
   L.idx = idx;
   L.count = count;
   L.idx_cap = idx_cap;
+  // scratch of the two-stage selection: behind the arrival counters, which stay untouched
+  const size_t off = ws_layout(units, d->D, 1).part_off;
+  const bool usable = ws && aligned16(ws) && ws_bytes > off;
+  L.scratch = usable ? static_cast<char*>(ws) + off : nullptr;
+  L.scratch_bytes = usable ? ws_bytes - off : 0;
   return launch_select(L, static_cast<hipStream_t>(stream));
 }
 
@@ -240,6 +262,8 @@ tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* 
   L.idx = idx;
   L.count = count;
   L.idx_cap = idx_cap;
+  L.scratch = static_cast<char*>(ws) + w.part_off;
+  L.scratch_bytes = ws_bytes - w.part_off;
   TB_TRY(launch_select(L, st));
 
   AttnLaunch A{d,   q,   K,   V,
@@ -253,12 +277,17 @@ tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* 
 size_t tb_workspace_bytes(int32_t op, const tb_cache_desc* d, int64_t max_count) {
   if (check_desc(d) != TB_OK || max_count < 0) return 0;
   const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
-  if (op == TB_OP_SELECT) return 0;  // the selection needs no global scratch
+  // two-stage selection of long rows (none for most shapes): max_count bounds the budget
+  const int64_t kk_bound = max_count < d->N ? max_count : d->N;
+  const size_t sel = select_scratch_bytes(units, select_plan(units, d->N, kk_bound));
+  const size_t sel_total = sel ? ws_layout(units, d->D, 1).part_off + align_up(sel, 256) : 0;
+  if (op == TB_OP_SELECT) return sel_total;
   if (op == TB_OP_ATTN || op == TB_OP_DECODE_STEP) {
     const AttnPlan plan = attn_plan(units, max_count, attn_tile_rows_per_wg(d->dtype, d->D));
     // sized for the largest split count a shorter list could get, so that one workspace serves
     // every call whose list is no longer than max_count
-    return ws_layout(units, d->D, plan.max_split).total;
+    const size_t att = ws_layout(units, d->D, plan.max_split).total;
+    return (op == TB_OP_DECODE_STEP && sel_total > att) ? sel_total : att;
   }
   return 0;
 }

@@ -20,7 +20,9 @@ constexpr int kCounterStrideWords = TB_COUNTER_STRIDE_WORDS;
 
 // Workspace layout (byte offsets), fixed by B*Hq so that all operations agree on it:
 //   [0, part_off)              uint32 arrival counters, one per (b,h), 256 B apart -- zero between calls
-//   [part_off, ...)            fp32 split-attention partials [B*Hq][nsplit][D+2]
+//   [part_off, ...)            fp32 split-attention partials [B*Hq][nsplit][D+2]; the two-stage
+//                              selection of long rows keeps its candidates in the same region
+//                              (it has finished before the attention of the same stream starts)
 struct WsLayout {
   size_t part_off, total;
 };
@@ -46,6 +48,21 @@ struct ScoreLaunch {
 };
 tb_status launch_score(const ScoreLaunch& a, hipStream_t st);
 
+// Long rows on few heads are selected in two stages so that more than one compute unit works
+// on a head: the row is cut into `chunks` pieces, each piece keeps its own top-kk (stage A, one
+// workgroup per piece), and the final kk are selected among the kept ones (stage B).
+// chunks == 1: one workgroup per row, no scratch.
+struct SelectPlan {
+  int chunks;
+  int64_t chunk_len;    // scores per piece (a multiple of the 4096-score workgroup tile)
+  int64_t cand_stride;  // capacity of a head's candidate arrays (a multiple of 4)
+};
+SelectPlan select_plan(int64_t units, int64_t N, int64_t kk);
+// candidate indices int32 [units][cand_stride] followed by candidate scores fp32 [units][cand_stride]
+inline size_t select_scratch_bytes(int64_t units, const SelectPlan& p) {
+  return p.chunks > 1 ? static_cast<size_t>(units) * p.cand_stride * 8 : 0;
+}
+
 struct SelectLaunch {
   int64_t units;
   int64_t N;
@@ -55,6 +72,8 @@ struct SelectLaunch {
   int32_t* idx;
   int32_t* count;
   int64_t idx_cap;
+  void* scratch;         // 16-byte aligned, or NULL
+  size_t scratch_bytes;  // below select_scratch_bytes(): one workgroup per row is used instead
 };
 tb_status launch_select(const SelectLaunch& a, hipStream_t st);
 

@@ -47,12 +47,28 @@ struct SelectArgs {
   const float* scores;
   int64_t score_stride;
   int64_t N;
-  int32_t kk, lo, hi;
+  int32_t kk, lo, hi;  // selection: the kk largest of the candidates [lo, hi)
   int32_t* idx;
   int32_t* count;
   int64_t idx_cap;
   int32_t tiles_per_wave;
+  // Two-stage selection of long rows.  Stage A (chunks > 1): workgroup (u, c) selects inside
+  // piece c of row u and writes the kept positions (as positions of the whole row) and their
+  // scores densely behind those of the pieces before it; no sink/window ranges, no count.
+  // Stage B (remap != NULL): the row is the candidate array of stage A; a kept position p is
+  // written as remap[p], and the sink/window ranges and the count are those of the original row.
+  int32_t chunks;
+  int64_t chunk_len;
+  float* cand_score;
+  const int32_t* remap;
+  int32_t emit_lo, emit_hi;  // the original row's candidate range (== lo, hi without stages)
+  int64_t emit_N;
 };
+
+// A score whose key is `key` (the inverse of score_key up to the folding of NaN and -0).
+__device__ inline float key_to_score(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
+}
 
 // The four scores at positions n0 .. n0+3 (n0 a multiple of 4) as one 128-bit load without any
 // branch, so that a thread's loads can all be in flight together.  A row's allocation covers
@@ -197,16 +213,41 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = tid / kWave;
-  const int u = blockIdx.x;
-  const float* s = a.scores + static_cast<int64_t>(u) * a.score_stride;
+  int u = blockIdx.x;
+  int lo = a.lo, hi = a.hi, kk = a.kk;
+  int64_t N = a.N;
+  int64_t row_off = 0;      // stage A: where this piece starts in the row
+  int64_t cand_off = 0;     // stage A: kept keys of the pieces before this one
+  if (a.chunks > 1) {
+    const int c = blockIdx.x % a.chunks;
+    u = blockIdx.x / a.chunks;
+    for (int cc = 0; cc <= c; ++cc) {
+      const int64_t base = cc * a.chunk_len;
+      int64_t n_c = a.N - base;
+      n_c = n_c < 0 ? 0 : (n_c > a.chunk_len ? a.chunk_len : n_c);
+      int64_t lo_c = a.lo - base, hi_c = a.hi - base;
+      lo_c = lo_c < 0 ? 0 : (lo_c > n_c ? n_c : lo_c);
+      hi_c = hi_c < lo_c ? lo_c : (hi_c > n_c ? n_c : hi_c);
+      const int64_t kk_c = a.kk < hi_c - lo_c ? a.kk : hi_c - lo_c;
+      if (cc < c) {
+        cand_off += kk_c;
+      } else {
+        row_off = base;
+        N = n_c;
+        lo = static_cast<int>(lo_c);
+        hi = static_cast<int>(hi_c);
+        kk = static_cast<int>(kk_c);
+      }
+    }
+  }
+  const float* s = a.scores + static_cast<int64_t>(u) * a.score_stride + row_off;
   int32_t* out = a.idx + static_cast<int64_t>(u) * a.idx_cap;
-  const int lo = a.lo, hi = a.hi, kk = a.kk;
   const int tpw = (NT > 0) ? NT : a.tiles_per_wave;
   const int64_t wbase = static_cast<int64_t>(wave) * tpw * kWaveTile + lane * 4;
   const bool refine = kk > 0 && kk < hi - lo;
 
   TB_MARK(0);
-  const int64_t last4 = a.N > 0 ? ((a.N - 1) & ~int64_t{3}) : 0;  // the vector that holds the last score
+  const int64_t last4 = N > 0 ? ((N - 1) & ~int64_t{3}) : 0;  // the vector that holds the last score
   uint32_t keys[NT > 0 ? NT : 1][4];
   if (NT > 0 && kk > 0) {
     float4 raw[NT > 0 ? NT : 1];  // every load of the thread is issued before the first is used
@@ -220,10 +261,21 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   if (tid < (kMaxLevels + 1) * 8) reinterpret_cast<uint32_t*>(s_found)[tid] = 0;
   if (tid == 0) s_nlist = 0;
 
-  // always-kept ranges: sink prefix [0, lo) and local window [hi, N)
-  for (int64_t n = tid; n < lo; n += kSelThreads) out[n] = static_cast<int32_t>(n);
-  for (int64_t n = hi + tid; n < a.N; n += kSelThreads) out[lo + kk + (n - hi)] = static_cast<int32_t>(n);
-  if (tid == 0) a.count[u] = static_cast<int32_t>(lo + kk + (a.N - hi));
+  // always-kept ranges: sink prefix [0, lo) and local window [hi, N) of the original row
+  int32_t* sel_out;
+  float* cand = nullptr;
+  const int32_t* remap = nullptr;
+  if (a.chunks > 1) {
+    sel_out = out + cand_off;
+    cand = a.cand_score + static_cast<int64_t>(u) * a.idx_cap + cand_off;
+  } else {
+    const int e_lo = a.emit_lo, e_hi = a.emit_hi;
+    for (int64_t n = tid; n < e_lo; n += kSelThreads) out[n] = static_cast<int32_t>(n);
+    for (int64_t n = e_hi + tid; n < a.emit_N; n += kSelThreads) out[e_lo + kk + (n - e_hi)] = static_cast<int32_t>(n);
+    if (tid == 0) a.count[u] = static_cast<int32_t>(e_lo + kk + (a.emit_N - e_hi));
+    sel_out = out + e_lo;
+    if (a.remap) remap = a.remap + static_cast<int64_t>(u) * a.score_stride;
+  }
   if (kk == 0) return;
 
   // visit every tile of this wave's span: body(j, keys of the tile)
@@ -492,7 +544,12 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   uint32_t base_eq = wave_entries_scan(s_weq, unused_total);
 
   // Pass B: position of a kept key = (#greater before it) + min(#equal before it, r_eq)
-  int32_t* sel_out = out + lo;
+  auto emit = [&](uint32_t pos, int32_t n, uint32_t key) {
+    if (pos < static_cast<uint32_t>(kk)) {
+      sel_out[pos] = remap ? remap[n] : static_cast<int32_t>(row_off) + n;
+      if (cand) cand[pos] = key_to_score(key);
+    }
+  };
   for_each_tile([&](int j, const uint32_t(&k4)[4]) {
     const uint32_t cnt = tile_count(k4);
     uint32_t excl;
@@ -511,7 +568,7 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         if (k4[c] > T) {
-          if (pos < static_cast<uint32_t>(kk)) sel_out[pos] = nn + c;
+          emit(pos, nn + c, k4[c]);
           ++pos;
         }
       }
@@ -521,8 +578,7 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
         const bool gt = k4[c] > T;
         const bool eq = (k4[c] == T) && T;
         if (gt || (eq && eq_before < r_eq)) {
-          const uint32_t pos = gt_before + (eq_before < r_eq ? eq_before : r_eq);
-          if (pos < static_cast<uint32_t>(kk)) sel_out[pos] = nn + c;
+          emit(gt_before + (eq_before < r_eq ? eq_before : r_eq), nn + c, k4[c]);
         }
         gt_before += gt ? 1u : 0u;
         eq_before += eq ? 1u : 0u;
@@ -532,6 +588,31 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
     base_eq += tot >> 16;
   });
   TB_MARK(6);
+}
+
+}  // namespace
+
+namespace {
+
+tb_status launch_one(const SelectArgs& a, int64_t workgroups, int64_t row_len, hipStream_t st) {
+  SelectArgs b = a;
+  const int32_t tiles = static_cast<int32_t>((row_len + kTileElts - 1) / kTileElts);  // per wave
+  b.tiles_per_wave = tiles;
+  dim3 grid(static_cast<unsigned>(workgroups));
+  dim3 block(kSelThreads);
+  if (tiles <= 1)
+    hipLaunchKernelGGL(select_kernel<1>, grid, block, 0, st, b);
+  else if (tiles <= 2)
+    hipLaunchKernelGGL(select_kernel<2>, grid, block, 0, st, b);
+  else if (tiles <= 4)
+    hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, st, b);
+  else if (tiles <= 8)
+    hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, st, b);
+  else if (tiles <= 16)
+    hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, st, b);
+  else
+    hipLaunchKernelGGL(select_kernel<0>, grid, block, 0, st, b);
+  return hip_status(hipGetLastError());
 }
 
 }  // namespace
@@ -548,23 +629,48 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   a.idx = L.idx;
   a.count = L.count;
   a.idx_cap = L.idx_cap;
-  const int32_t tiles = static_cast<int32_t>((L.N + kTileElts - 1) / kTileElts);  // per wave
-  a.tiles_per_wave = tiles;
-  dim3 grid(static_cast<unsigned>(L.units));
-  dim3 block(kSelThreads);
-  if (tiles <= 1)
-    hipLaunchKernelGGL(select_kernel<1>, grid, block, 0, st, a);
-  else if (tiles <= 2)
-    hipLaunchKernelGGL(select_kernel<2>, grid, block, 0, st, a);
-  else if (tiles <= 4)
-    hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, st, a);
-  else if (tiles <= 8)
-    hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, st, a);
-  else if (tiles <= 16)
-    hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, st, a);
-  else
-    hipLaunchKernelGGL(select_kernel<0>, grid, block, 0, st, a);
-  return hip_status(hipGetLastError());
+  a.chunks = 1;
+  a.chunk_len = 0;
+  a.cand_score = nullptr;
+  a.remap = nullptr;
+  a.emit_lo = L.lo;
+  a.emit_hi = L.hi;
+  a.emit_N = L.N;
+  const SelectPlan plan = select_plan(L.units, L.N, L.kk);
+  if (plan.chunks <= 1 || !L.scratch || L.scratch_bytes < select_scratch_bytes(L.units, plan))
+    return launch_one(a, L.units, L.N, st);
+
+  // stage A: every piece keeps its own top-kk; positions and scores land in the scratch arrays
+  int32_t* cand_idx = static_cast<int32_t*>(L.scratch);
+  float* cand_score = reinterpret_cast<float*>(cand_idx + L.units * plan.cand_stride);
+  SelectArgs sa = a;
+  sa.chunks = plan.chunks;
+  sa.chunk_len = plan.chunk_len;
+  sa.idx = cand_idx;
+  sa.idx_cap = plan.cand_stride;
+  sa.cand_score = cand_score;
+  sa.count = nullptr;
+  const tb_status rc = launch_one(sa, L.units * plan.chunks, plan.chunk_len, st);
+  if (rc != TB_OK) return rc;
+  // stage B: the kk largest among what the pieces kept (the same host arithmetic as the kernel's)
+  int64_t n_cand = 0;
+  for (int c = 0; c < plan.chunks; ++c) {
+    const int64_t base = c * plan.chunk_len;
+    int64_t n_c = L.N - base;
+    n_c = n_c < 0 ? 0 : (n_c > plan.chunk_len ? plan.chunk_len : n_c);
+    int64_t lo_c = L.lo - base, hi_c = L.hi - base;
+    lo_c = lo_c < 0 ? 0 : (lo_c > n_c ? n_c : lo_c);
+    hi_c = hi_c < lo_c ? lo_c : (hi_c > n_c ? n_c : hi_c);
+    n_cand += L.kk < hi_c - lo_c ? L.kk : hi_c - lo_c;
+  }
+  SelectArgs sb = a;
+  sb.scores = cand_score;
+  sb.score_stride = plan.cand_stride;
+  sb.N = n_cand;
+  sb.lo = 0;
+  sb.hi = static_cast<int32_t>(n_cand);
+  sb.remap = cand_idx;
+  return launch_one(sb, L.units, n_cand, st);
 }
 
 }  // namespace tb

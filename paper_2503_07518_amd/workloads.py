@@ -86,6 +86,12 @@ C5 = DecodeConfig("C5_long_context", B=4, Hq=64, Hkv=8, D=128, N=131072, Dimp=32
                   heavy_per_kv_head=655, zipf_kimp=True)
 CONFIGS = {c.name: c for c in (C1, C2, C3, C4, C5)}
 
+# Beyond the benchmark definition: the offloaded-cache regime of the paper's efficiency section
+# (contexts of 256K and more with K/V in host memory; an 8K-token budget there).
+C6 = DecodeConfig("C6_offload_1m", B=1, Hq=32, Hkv=8, D=128, N=1 << 20, Dimp=32, k=8192, dtype="bf16",
+                  heavy_per_kv_head=819)
+EXTRA_CONFIGS = {c.name: c for c in (C6,)}
+
 
 def _seed(cfg: DecodeConfig, layer: int, tensor: str, seed: int) -> int:
     return zlib.crc32(f"{cfg.name}/{layer}/{tensor}/{seed}".encode()) & 0x7FFFFFFF

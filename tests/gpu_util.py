@@ -52,7 +52,7 @@ def gpu_select(scores, N, k, sink=0, window=0, cap=None, ws=None, Hkv=None):
     d.k_stride_n = d.v_stride_n = 128
     d.ki_stride_n = 32
     if ws is None:
-        ws = tb.new_workspace(tb.TB_OP_SELECT, d)
+        ws = tb.new_workspace(tb.TB_OP_SELECT, d, need)  # long rows on few heads: two-stage selection
     tb.tb_select_topk(d, scores, k, sink, window, idx, cnt, ws)
     return idx, cnt
 

@@ -125,8 +125,8 @@ def test_score(oracle, dtype, B, Hq, Hkv, Dimp, N):
 
 # --------------------------------------------------------------------------- selection
 
-def check_select(oracle, scores_t, N, k, sink, window):
-    idx, cnt = gpu_select(scores_t, N, k, sink, window)
+def check_select(oracle, scores_t, N, k, sink, window, ws=None):
+    idx, cnt = gpu_select(scores_t, N, k, sink, window, ws=ws)
     torch.cuda.synchronize()
     s_np = np_of(scores_t)[:, :, :N]
     ridx, rcnt = oracle.select_topk(s_np, k, sink, window)
@@ -158,16 +158,27 @@ def test_select_sizes_random_scores(oracle, N):
 ])
 def test_select_streamed_rows(oracle, N, ks):
     say(f"select streamed N={N}")
+    from paper_2503_07518_amd import binding as tb
     scores = randn((1, 2, (N + 3) // 4 * 4), torch.float32, 200 + N % 1000)
-    for k in ks:
-        check_select(oracle, scores, N, k, 0, 0)
-    check_select(oracle, scores, N, ks[0], 128, 256)
-    # heavy ties around the threshold and a sorted row (every candidate in one wave's span)
+    d = tb.tb_cache_desc()
+    d.B, d.Hq, d.Hkv, d.D, d.Dimp, d.dtype, d.N = 1, 2, 2, 128, 32, tb.TB_F32, N
+    d.k_stride_n = d.v_stride_n = 128
+    d.ki_stride_n = 32
+    assert tb.tb_workspace_bytes(tb.TB_OP_SELECT, d, ks[0]) > 0, "a long row on two heads is cut into pieces"
+    # with the workspace that tb_workspace_bytes asks for, the row is selected piecewise by
+    # several workgroups; with a smaller one, a single workgroup streams the whole row
+    small = torch.zeros(256, dtype=torch.uint8, device=DEV)
     g = torch.Generator().manual_seed(N)
-    tied = torch.randint(0, 50, scores.shape, generator=g).to(torch.float32)
-    check_select(oracle, tied.to(DEV), N, ks[0], 0, 0)
-    asc = torch.arange(scores.shape[-1], dtype=torch.float32).view(1, 1, -1)
-    check_select(oracle, asc.to(DEV), N, ks[0], 0, 0)
+    tied = torch.randint(0, 50, scores.shape, generator=g).to(torch.float32).to(DEV)  # heavy ties at the threshold
+    asc = torch.arange(scores.shape[-1], dtype=torch.float32).view(1, 1, -1).to(DEV)  # every kept key in one span
+    for ws in (None, small):
+        for k in ks:
+            check_select(oracle, scores, N, k, 0, 0, ws=ws)
+        check_select(oracle, scores, N, ks[0], 128, 256, ws=ws)
+        check_select(oracle, tied, N, ks[0], 0, 0, ws=ws)
+        check_select(oracle, tied, N, ks[-1], 3, 5, ws=ws)
+        check_select(oracle, asc, N, ks[0], 0, 0, ws=ws)
+        check_select(oracle, -asc, N, ks[0], 2, 0, ws=ws)
 
 
 @pytest.mark.parametrize("N", [777, 9000, 66000])
