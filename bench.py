@@ -86,10 +86,12 @@ class LayerBuffers:
         return sum(t.numel() * t.element_size() for t in (self.K, self.V, self.Kimp, self.scores, self.idx))
 
 
-def time_interval_loop(cfg, tb, workloads, torch, replays=5):
+def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False):
     """The prediction-interval loop of the config (cfg.steps decode steps, a prediction every
     cfg.P steps, neighbours of radius cfg.radius on the steps in between) as one HIP graph:
-    mean time per step, and the rows that attention gathers on the two kinds of step."""
+    mean time per step, and the rows that attention gathers on the two kinds of step.
+    buffered: the widened selection is migrated into per-query-head buffers on prediction steps
+    (the paper's Important Buffer) and the other steps read the buffers instead of gathering."""
     from paper_2503_07518_amd import interval
 
     data = workloads.make_layer(cfg, layer=1, seed=0, device="cuda")
@@ -100,7 +102,7 @@ def time_interval_loop(cfg, tb, workloads, torch, replays=5):
     qis = [data["q_imp"][t].contiguous() for t in range(cfg.steps)]
 
     dec = interval.IntervalDecoder(K, V, W, Kimp, cfg.Hq, cfg.k, cfg.P, cfg.radius, sink=cfg.sink,
-                                   window=cfg.window, sm_scale=cfg.sm_scale)
+                                   window=cfg.window, sm_scale=cfg.sm_scale, buffered=buffered)
 
     def loop():
         dec.N_pred = dec.projected_upto = None  # the cache is back at its post-prefill length
@@ -135,13 +137,27 @@ def time_interval_loop(cfg, tb, workloads, torch, replays=5):
     desc = tb.make_desc(N_last, cfg.Hq, K=K, V=V, Kimp=Kimp)
     e0.record(cur)
     for _ in range(20):
-        tb.tb_sparse_decode_attn(desc, qs[t_last], K, V, dec.exp_idx, dec.exp_cnt, dec.exp_cap, cfg.sm_scale, dec.out,
-                                 dec.lse, dec.ws, tail_begin=dec.N_pred, tail_end=N_last)
+        if buffered:
+            tb.tb_buffered_decode_attn(desc, qs[t_last], dec.Kbuf, dec.Vbuf, dec.exp_cnt, dec.exp_cap, K, V,
+                                       cfg.sm_scale, dec.out, dec.lse, dec.ws, tail_begin=dec.N_pred, tail_end=N_last)
+        else:
+            tb.tb_sparse_decode_attn(desc, qs[t_last], K, V, dec.exp_idx, dec.exp_cnt, dec.exp_cap, cfg.sm_scale,
+                                     dec.out, dec.lse, dec.ws, tail_begin=dec.N_pred, tail_end=N_last)
     e1.record(cur)
     torch.cuda.synchronize()
     us_reuse = e0.elapsed_time(e1) * 1e3 / 20
     reuse_bytes = (exp_rows + cfg.B * cfg.Hq * (N_last - dec.N_pred)) * 2 * cfg.D * cfg.elt_bytes
+    us_migrate = None
+    if buffered:
+        e0.record(cur)
+        for _ in range(10):
+            tb.tb_gather_kv(desc, K, V, dec.exp_idx, dec.exp_cnt, dec.exp_cap, dec.Kbuf, dec.Vbuf)
+        e1.record(cur)
+        torch.cuda.synchronize()
+        us_migrate = e0.elapsed_time(e1) * 1e3 / 10
     return {
+        "attention_reads": "migrated buffers" if buffered else "cache rows (fused gather)",
+        "migration_us": None if us_migrate is None else round(us_migrate, 3),
         "steps": cfg.steps, "P": cfg.P, "radius": cfg.radius, "prediction_steps": n_pred,
         "reuse_steps": cfg.steps - n_pred, "us_per_step_mean": round(us_loop / cfg.steps, 3),
         "us_loop": round(us_loop, 1),
@@ -327,6 +343,7 @@ def main():
         result.pop("project_bulk")
     if cfg.P > 1:
         result["interval_loop"] = time_interval_loop(cfg, tb, workloads, torch)
+        result["interval_loop_buffered"] = time_interval_loop(cfg, tb, workloads, torch, buffered=True)
 
     if not args.no_cpu_baseline:
         import numpy as np

@@ -115,6 +115,26 @@ tb_status tb_sparse_decode_attn(const tb_cache_desc* desc, const void* q, const 
                                 int64_t tail_begin, int64_t tail_end, float sm_scale, float* out, float* lse,
                                 void* ws, size_t ws_bytes, void* stream);
 
+/* Migration of selected rows into the "Important Buffer" (Sec. 3.3 "Inference Setup": the
+ * paper keeps the attended tokens in contiguous buffers and copies the selection there on
+ * prediction steps).  Kbuf/Vbuf[b,h,i,:] = K/V[b,h/g,idx[b,h,i],:] for i < min(count[b,h], max_count).
+ * Kbuf, Vbuf: [B][Hq][buf_cap][D] contiguous, element type of the cache, buf_cap >= max_count;
+ * rows at and beyond the count are left untouched.  The buffers are per *query* head, because
+ * every query head selects its own tokens. */
+tb_status tb_gather_kv(const tb_cache_desc* desc, const void* K, const void* V, const int32_t* idx,
+                       const int32_t* count, int64_t idx_cap, int64_t max_count, void* Kbuf, void* Vbuf,
+                       int64_t buf_cap, void* stream);
+
+/* tb_sparse_decode_attn over rows that tb_gather_kv has migrated: the rows 0 .. count[b,h]-1 of
+ * the per-query-head buffers (no index list is read) followed by the dense range
+ * [tail_begin, tail_end) of the cache K, V (the local window of tokens appended since the
+ * migration).  Same result, bit for bit, as tb_sparse_decode_attn with the list the buffers
+ * were filled from.  ws: tb_workspace_bytes(TB_OP_ATTN, ...). */
+tb_status tb_buffered_decode_attn(const tb_cache_desc* desc, const void* q, const void* Kbuf, const void* Vbuf,
+                                  int64_t buf_cap, const int32_t* count, int64_t max_count, const void* K,
+                                  const void* V, int64_t tail_begin, int64_t tail_end, float sm_scale,
+                                  float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
+
 /* One prediction step in a single enqueue: tb_score -> tb_select_topk -> tb_sparse_decode_attn
  * with one validation pass and one launch plan.  Results (scores, idx, count, out, lse) are
  * identical to calling the three entry points one after the other.

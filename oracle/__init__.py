@@ -207,6 +207,26 @@ def sparse_decode_attn(q, K, V, idx, count, dtype, sm_scale: float) -> Tuple[np.
     return out, lse
 
 
+def gather_kv(K, V, idx, count, buf_cap: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Migration of selected rows into per-query-head buffers (Sec. 3.3, the Important Buffer):
+    buf[b,h,i,:] = cache[b, h // g, idx[b,h,i], :] for i < count[b,h]; the rest stays zero.
+    Written out as the definition, one (b, h) at a time."""
+    B, Hkv, N, D = K.shape
+    idx = np.asarray(idx)
+    count = np.asarray(count)
+    Hq = idx.shape[1]
+    g = Hq // Hkv
+    Kbuf = np.zeros((B, Hq, buf_cap, D), dtype=K.dtype)
+    Vbuf = np.zeros((B, Hq, buf_cap, D), dtype=V.dtype)
+    for b in range(B):
+        for h in range(Hq):
+            c = int(count[b, h])
+            rows = idx[b, h, :c].astype(np.int64)
+            Kbuf[b, h, :c] = K[b, h // g, rows]
+            Vbuf[b, h, :c] = V[b, h // g, rows]
+    return Kbuf, Vbuf
+
+
 def dense_decode_attn(q, K, V, dtype, sm_scale: float) -> np.ndarray:
     et = _elt(dtype)
     q = _arr(q, et)

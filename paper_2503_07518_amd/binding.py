@@ -23,7 +23,7 @@ TB_OP_SELECT, TB_OP_ATTN, TB_OP_DECODE_STEP = 1, 2, 3
 
 EXPORTS = (
     "tb_project_keys", "tb_score", "tb_select_topk", "tb_expand_neighbors", "tb_sparse_decode_attn",
-    "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_status_string", "tb_version",
+    "tb_gather_kv", "tb_buffered_decode_attn", "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_status_string", "tb_version",
 )
 
 
@@ -65,6 +65,8 @@ def load_library() -> ctypes.CDLL:
     L.tb_sparse_decode_attn.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, i64, f32, vp, vp, vp, sz, vp]
     L.tb_decode_step.argtypes = [dp, vp, vp, f32, vp, vp, vp, i32, i32, i32, f32, vp, i64, vp, vp, i64, vp, vp,
                                  vp, sz, vp]
+    L.tb_gather_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, vp, vp, i64, vp]
+    L.tb_buffered_decode_attn.argtypes = [dp, vp, vp, vp, i64, vp, i64, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
     L.tb_workspace_bytes.argtypes = [i32, dp, i64]
     L.tb_workspace_bytes.restype = sz
     L.tb_workspace_init.argtypes = [vp, sz, vp]
@@ -166,6 +168,23 @@ def tb_select_topk(desc, scores, k: int, sink: int, window: int, idx, count, ws,
     _check(load_library().tb_select_topk(ctypes.byref(desc), _ptr(scores), scores.stride(-2), k, sink, window,
                                          _ptr(idx), _ptr(count), idx.stride(-2), _ptr(ws),
                                          ws.numel() * ws.element_size(), _stream(stream)), "tb_select_topk")
+
+
+def tb_gather_kv(desc, K, V, idx, count, max_count: int, Kbuf, Vbuf, stream=None) -> None:
+    assert Kbuf.is_contiguous() and Vbuf.is_contiguous() and Kbuf.shape == Vbuf.shape
+    _check(load_library().tb_gather_kv(ctypes.byref(desc), _ptr(K), _ptr(V), _ptr(idx), _ptr(count), idx.stride(-2),
+                                       max_count, _ptr(Kbuf), _ptr(Vbuf), Kbuf.shape[2], _stream(stream)),
+           "tb_gather_kv")
+
+
+def tb_buffered_decode_attn(desc, q, Kbuf, Vbuf, count, max_count: int, K, V, sm_scale: float, out, lse, ws,
+                            tail_begin: int = 0, tail_end: int = 0, stream=None) -> None:
+    assert Kbuf.is_contiguous() and Vbuf.is_contiguous() and Kbuf.shape == Vbuf.shape
+    _check(load_library().tb_buffered_decode_attn(ctypes.byref(desc), _ptr(q), _ptr(Kbuf), _ptr(Vbuf), Kbuf.shape[2],
+                                                  _ptr(count), max_count, _ptr(K), _ptr(V), tail_begin, tail_end,
+                                                  sm_scale, _ptr(out), _ptr(lse), _ptr(ws),
+                                                  ws.numel() * ws.element_size(), _stream(stream)),
+           "tb_buffered_decode_attn")
 
 
 def tb_expand_neighbors(B: int, Hq: int, N: int, radius: int, mode: int, idx_in, count_in, idx_out, count_out,

@@ -234,6 +234,47 @@ tb_status tb_sparse_decode_attn(const tb_cache_desc* d, const void* q, const voi
   return launch_attn(L, static_cast<hipStream_t>(stream));
 }
 
+tb_status tb_gather_kv(const tb_cache_desc* d, const void* K, const void* V, const int32_t* idx, const int32_t* count,
+                       int64_t idx_cap, int64_t max_count, void* Kbuf, void* Vbuf, int64_t buf_cap, void* stream) {
+  TB_TRY(check_desc(d));
+  if (!K || !V || !idx || !count || !Kbuf || !Vbuf) return TB_ERR_INVALID_ARG;
+  if (idx_cap < 0 || max_count < 0 || max_count > idx_cap || max_count > buf_cap) return TB_ERR_INVALID_ARG;
+  if (d->N == 0 && max_count > 0) return TB_ERR_INVALID_ARG;
+  TB_TRY(check_strides(d, d->k_stride_b, d->k_stride_h, d->k_stride_n, d->D));
+  TB_TRY(check_strides(d, d->v_stride_b, d->v_stride_h, d->v_stride_n, d->D));
+  if (!aligned16(K) || !aligned16(V) || !aligned16(Kbuf) || !aligned16(Vbuf)) return TB_ERR_UNSUPPORTED;
+  if (max_count > (int64_t{1} << 30)) return TB_ERR_UNSUPPORTED;
+  GatherLaunch L{d, K, V, idx, count, idx_cap, max_count, Kbuf, Vbuf, buf_cap};
+  return launch_gather(L, static_cast<hipStream_t>(stream));
+}
+
+tb_status tb_buffered_decode_attn(const tb_cache_desc* d, const void* q, const void* Kbuf, const void* Vbuf,
+                                  int64_t buf_cap, const int32_t* count, int64_t max_count, const void* K,
+                                  const void* V, int64_t tail_begin, int64_t tail_end, float sm_scale, float* out,
+                                  float* lse, void* ws, size_t ws_bytes, void* stream) {
+  if (!Kbuf || !Vbuf || buf_cap < 0 || max_count > buf_cap) return TB_ERR_INVALID_ARG;
+  // the list itself is not read: its place in the argument check is taken by the count array
+  TB_TRY(check_attn_args(d, q, K, V, count, count, buf_cap, max_count, tail_begin, tail_end, out));
+  if (!aligned16(Kbuf) || !aligned16(Vbuf)) return TB_ERR_UNSUPPORTED;
+  const int64_t elt = d->dtype == TB_F32 ? 4 : 2;
+  if (buf_cap * d->D * elt >= (int64_t{1} << 32)) return TB_ERR_UNSUPPORTED;  // 32-bit offsets inside a head's buffer
+  const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
+  if (units == 0) return TB_OK;
+  const int64_t rows = max_count + (tail_end - tail_begin);
+  const AttnPlan plan = attn_plan(units, rows, attn_tile_rows_per_wg(d->dtype, d->D));
+  const WsLayout w = ws_layout(units, d->D, plan.nsplit);
+  if (!ws || !aligned16(ws) || ws_bytes < w.total) return TB_ERR_WORKSPACE;
+  AttnLaunch L{d,   q,   K,   V,
+               nullptr, count, buf_cap, max_count, tail_begin, tail_end,
+               sm_scale, out, lse,
+               reinterpret_cast<float*>(static_cast<char*>(ws) + w.part_off),
+               reinterpret_cast<uint32_t*>(ws), plan};
+  L.Kbuf = Kbuf;
+  L.Vbuf = Vbuf;
+  L.buf_cap = buf_cap;
+  return launch_attn(L, static_cast<hipStream_t>(stream));
+}
+
 tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* Kimp, float score_scale,
                          const void* q, const void* K, const void* V, int32_t k, int32_t sink, int32_t window,
                          float sm_scale, float* scores, int64_t score_stride, int32_t* idx, int32_t* count,

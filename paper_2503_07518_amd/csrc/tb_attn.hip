@@ -47,11 +47,18 @@ struct AttnArgs {
   float* partials;
   uint32_t* counters;
   int32_t Hq, g, rows_per_wg, nsplit;
+  // buffered form: the listed rows have been copied to per-query-head buffers
+  // [B][Hq][buf_cap][D] in list order (slot i of the list is buffer row i); idx is unused
+  const void* Kbuf;
+  const void* Vbuf;
+  int64_t buf_cap;
 };
+
+constexpr int32_t kTailFlag = 0x40000000;  // buffered form: the row number refers to the cache, not the buffer
 
 __device__ inline float exp2_safe(float d) { return __builtin_amdgcn_exp2f(d); }
 
-template <typename T, int D>
+template <typename T, int D, bool BUF>
 __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_kernel(AttnArgs a) {
   constexpr int EPL = Pack16<T>::kElts;    // elements per lane
   constexpr int LPR = D / EPL;             // lanes per row
@@ -86,7 +93,13 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
                                                    hkv * a.v_stride_h) + sub * 16;
   const uint32_t k_row_bytes = static_cast<uint32_t>(a.k_stride_n * sizeof(T));
   const uint32_t v_row_bytes = static_cast<uint32_t>(a.v_stride_n * sizeof(T));
-  const int32_t* list = a.idx + u * a.idx_cap;
+  const int32_t* list = BUF ? nullptr : a.idx + u * a.idx_cap;
+  const char* kbuf = nullptr;
+  const char* vbuf = nullptr;
+  if (BUF) {
+    kbuf = reinterpret_cast<const char*>(static_cast<const T*>(a.Kbuf) + u * a.buf_cap * D) + sub * 16;
+    vbuf = reinterpret_cast<const char*>(static_cast<const T*>(a.Vbuf) + u * a.buf_cap * D) + sub * 16;
+  }
 
   float qv[EPL];
   Pack16<T>::load(static_cast<const T*>(a.q) + u * D + sub * EPL, qv);
@@ -104,6 +117,11 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
   auto fetch_rows = [&](int64_t t0) -> int32_t {
     const int64_t i = t0 + lane;
     if (lane < TILE && i < w_end) {
+      if (BUF) {  // slot i of the list is row i of the buffer; the tail is read from the cache
+        if (i < cnt) return static_cast<int32_t>(i);
+        const int64_t n = a.tail_begin + (i - cnt);
+        return static_cast<int32_t>(n < 0 ? 0 : (n >= a.N ? a.N - 1 : n)) | kTailFlag;
+      }
       int64_t n = (i < cnt) ? static_cast<int64_t>(list[i]) : a.tail_begin + (i - cnt);
       n = n < 0 ? 0 : (n >= a.N ? a.N - 1 : n);  // keep the gather inside the cache whatever the list holds
       return static_cast<int32_t>(n);
@@ -111,7 +129,14 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     return -1;
   };
   int32_t n_next;
-  {
+  if (BUF) {
+    int64_t cnt_now = a.count[u];
+    cnt_now = cnt_now < 0 ? 0 : (cnt_now > a.max_count ? a.max_count : cnt_now);
+    cnt = cnt_now;
+    total = cnt + (a.tail_end - a.tail_begin);
+    w_end = (w_beg0 + rows_per_wave < total) ? w_beg0 + rows_per_wave : total;
+    n_next = fetch_rows(w_beg0);
+  } else {
     // first tile: the list entry is read without waiting for the count (the slot is inside
     // the list's capacity whatever the count is) and sorted out afterwards
     const int64_t i = w_beg0 + lane;
@@ -134,11 +159,20 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     for (int t = 0; t < kLoadsPerTile; ++t) {
       const int32_t n = __shfl(n_mine, t * GPW + grp, kWave);
       valid[t] = n >= 0;
-      const uint32_t row = valid[t] ? static_cast<uint32_t>(n) : 0u;
       // 32-bit byte offsets from a per-workgroup base (the host checks that a head's slab is
       // below 4 GiB): one address register per gather instead of two
-      kraw[t] = Pack16<T>::load_raw(kbase + row * k_row_bytes);
-      vraw[t] = Pack16<T>::load_raw(vbase + row * v_row_bytes);
+      if (BUF) {
+        const bool tail = valid[t] && (n & kTailFlag);
+        const uint32_t row = valid[t] ? static_cast<uint32_t>(n & (kTailFlag - 1)) : 0u;
+        const char* kp = tail ? kbase + row * k_row_bytes : kbuf + row * static_cast<uint32_t>(D * sizeof(T));
+        const char* vp = tail ? vbase + row * v_row_bytes : vbuf + row * static_cast<uint32_t>(D * sizeof(T));
+        kraw[t] = Pack16<T>::load_raw(kp);
+        vraw[t] = Pack16<T>::load_raw(vp);
+      } else {
+        const uint32_t row = valid[t] ? static_cast<uint32_t>(n) : 0u;
+        kraw[t] = Pack16<T>::load_raw(kbase + row * k_row_bytes);
+        vraw[t] = Pack16<T>::load_raw(vbase + row * v_row_bytes);
+      }
     }
     n_next = fetch_rows(t0 + TILE);
     // every gather of the tile is in flight before the first one is consumed
@@ -331,8 +365,14 @@ tb_status launch_td(const AttnLaunch& L, hipStream_t st) {
   a.g = d.Hq / d.Hkv;
   a.rows_per_wg = L.plan.rows_per_wg;
   a.nsplit = L.plan.nsplit;
+  a.Kbuf = L.Kbuf;
+  a.Vbuf = L.Vbuf;
+  a.buf_cap = L.buf_cap;
   dim3 grid(L.plan.nsplit, d.Hq, d.B);
-  hipLaunchKernelGGL((attn_kernel<T, D>), grid, dim3(kAttnThreads), 0, st, a);
+  if (L.Kbuf)
+    hipLaunchKernelGGL((attn_kernel<T, D, true>), grid, dim3(kAttnThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL((attn_kernel<T, D, false>), grid, dim3(kAttnThreads), 0, st, a);
   return hip_status(hipGetLastError());
 }
 

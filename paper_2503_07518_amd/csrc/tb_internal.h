@@ -91,7 +91,25 @@ struct AttnLaunch {
   float* partials;
   uint32_t* counters;
   AttnPlan plan;
+  // buffered form (Kbuf != NULL): list slot i is row i of the per-query-head buffers
+  const void* Kbuf = nullptr;
+  const void* Vbuf = nullptr;
+  int64_t buf_cap = 0;
 };
+
+// Copies the listed rows of K and V into per-query-head buffers [B][Hq][buf_cap][D].
+struct GatherLaunch {
+  const tb_cache_desc* desc;
+  const void* K;
+  const void* V;
+  const int32_t* idx;
+  const int32_t* count;
+  int64_t idx_cap, max_count;
+  void* Kbuf;
+  void* Vbuf;
+  int64_t buf_cap;
+};
+tb_status launch_gather(const GatherLaunch& a, hipStream_t st);
 int attn_tile_rows_per_wg(int dtype, int D);
 tb_status launch_attn(const AttnLaunch& a, hipStream_t st);
 

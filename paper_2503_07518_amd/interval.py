@@ -6,6 +6,10 @@ newly appended keys are projected, the whole cache is scored, the top-k selectio
 attention runs on it; the selection widened by its neighbours is kept.  On the other steps
 attention runs on the kept list plus the dense tail of rows appended since the prediction (the
 local window is refreshed every step), and nothing else is touched.
+
+With ``buffered=True`` the widened selection is migrated into per-query-head buffers on the
+prediction step (the paper's Important Buffer, Sec. 3.3) and the other steps attend over the
+buffers plus the dense tail; the fused form gathers the rows from the cache on every step.
 """
 from __future__ import annotations
 
@@ -16,7 +20,8 @@ from . import binding as tb
 
 class IntervalDecoder:
     def __init__(self, K, V, W, Kimp, Hq: int, k: int, P: int, radius: int, sink: int = 0, window: int = 0,
-                 sm_scale: float = 1.0, score_scale: float = 1.0, mode: int = 0, expand_on_predict: bool = False):
+                 sm_scale: float = 1.0, score_scale: float = 1.0, mode: int = 0, expand_on_predict: bool = False,
+                 buffered: bool = False):
         self.K, self.V, self.W, self.Kimp = K, V, W, Kimp
         self.B, self.Hkv, self.Ncap, self.D = K.shape
         self.Hq, self.k, self.P, self.radius = Hq, k, P, radius
@@ -38,6 +43,10 @@ class IntervalDecoder:
         self.ws = tb.new_workspace(tb.TB_OP_DECODE_STEP, desc, self.exp_cap + P)
         self.N_pred = None
         self.projected_upto = None
+        self.buffered = buffered
+        if buffered:
+            self.Kbuf = torch.empty((B, Hq, self.exp_cap, self.D), dtype=K.dtype, device=dev)
+            self.Vbuf = torch.empty_like(self.Kbuf)
 
     def step(self, t: int, N_t: int, q: torch.Tensor, q_imp: torch.Tensor):
         """Returns (out, lse) views valid until the next call."""
@@ -53,9 +62,15 @@ class IntervalDecoder:
             tb.tb_expand_neighbors(self.B, self.Hq, N_t, self.radius, self.mode, self.idx, self.cnt, self.exp_idx,
                                    self.exp_cnt)
             self.N_pred = N_t
+            if self.buffered:
+                tb.tb_gather_kv(desc, self.K, self.V, self.exp_idx, self.exp_cnt, self.exp_cap, self.Kbuf, self.Vbuf)
             if self.expand_on_predict:
                 tb.tb_sparse_decode_attn(desc, q, self.K, self.V, self.exp_idx, self.exp_cnt, self.exp_cap,
                                          self.sm_scale, self.out, self.lse, self.ws)
+        elif self.buffered:
+            tb.tb_buffered_decode_attn(desc, q, self.Kbuf, self.Vbuf, self.exp_cnt, self.exp_cap, self.K, self.V,
+                                       self.sm_scale, self.out, self.lse, self.ws, tail_begin=self.N_pred,
+                                       tail_end=N_t)
         else:
             tb.tb_sparse_decode_attn(desc, q, self.K, self.V, self.exp_idx, self.exp_cnt, self.exp_cap,
                                      self.sm_scale, self.out, self.lse, self.ws, tail_begin=self.N_pred, tail_end=N_t)

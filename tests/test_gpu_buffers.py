@@ -1,0 +1,94 @@
+"""The paper's physical buffer layout (Sec. 3.3): migration of the selected rows into
+per-query-head buffers and attention over the buffers plus the local window, against the
+oracle and against the fused-gather attention (which must agree bit for bit)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import DEV, dtype_name, gpu_attn, np_of
+from paper_2503_07518_amd import binding as tb, interval, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def make_lists(B, Hq, N, cap, seed, full=False):
+    g = torch.Generator().manual_seed(seed)
+    idx = torch.stack([torch.stack([torch.randperm(N, generator=g)[:cap].sort().values for _ in range(Hq)])
+                       for _ in range(B)]).to(torch.int32)
+    cnt = torch.full((B, Hq), cap, dtype=torch.int32) if full else torch.randint(0, cap + 1, (B, Hq), generator=g).to(torch.int32)
+    cnt[0, 0] = cap
+    if Hq > 1:
+        cnt[0, 1] = 0
+    return idx.to(DEV), cnt.to(DEV)
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,D,N,cap", [
+    (torch.bfloat16, 2, 8, 2, 128, 3000, 517),
+    (torch.float32, 1, 4, 4, 64, 700, 130),
+    (torch.bfloat16, 1, 4, 1, 64, 90, 64),
+    (torch.float32, 1, 2, 2, 128, 33, 1),
+])
+def test_gather_kv_and_buffered_attention(oracle, dtype, B, Hq, Hkv, D, N, cap):
+    say(f"gather + buffered attention dtype={dtype} B={B} Hq={Hq} Hkv={Hkv} D={D} N={N} cap={cap}")
+    g = torch.Generator().manual_seed(11)
+    K = torch.randn((B, Hkv, N, D), generator=g).to(dtype).to(DEV)
+    V = torch.randn((B, Hkv, N, D), generator=g).to(dtype).to(DEV)
+    q = torch.randn((B, Hq, D), generator=g).to(dtype).to(DEV)
+    idx, cnt = make_lists(B, Hq, N - 8, cap, 12)
+    buf_cap = cap + 3
+    Kbuf = torch.full((B, Hq, buf_cap, D), 7.0, dtype=dtype, device=DEV)
+    Vbuf = torch.full((B, Hq, buf_cap, D), 7.0, dtype=dtype, device=DEV)
+    d = tb.make_desc(N, Hq, K=K, V=V)
+    tb.tb_gather_kv(d, K, V, idx, cnt, cap, Kbuf, Vbuf)
+    torch.cuda.synchronize()
+    rK, rV = oracle.gather_kv(np_of(K), np_of(V), np_of(idx), np_of(cnt), buf_cap)
+    mask = (np.arange(buf_cap)[None, None, :] < np_of(cnt)[..., None])[..., None]
+    seven = np_of(torch.full((1,), 7.0, dtype=dtype))[0]
+    assert np.array_equal(np.where(mask, np_of(Kbuf), 0), rK) and np.array_equal(np.where(mask, np_of(Vbuf), 0), rV)
+    assert np.all(np.where(mask, seven, np_of(Kbuf)) == seven), "rows beyond the count stay untouched"
+
+    sm = 1.0 / math.sqrt(D)
+    tail = (N - 8, N - 1)
+    ws = tb.new_workspace(tb.TB_OP_ATTN, d, cap + 7)
+    out = torch.full((B, Hq, D), float("nan"), dtype=torch.float32, device=DEV)
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    tb.tb_buffered_decode_attn(d, q, Kbuf, Vbuf, cnt, cap, K, V, sm, out, lse, ws, tail[0], tail[1])
+    fused_out, fused_lse = gpu_attn(q, K, V, idx, cnt, N, sm, max_count=cap, tail=tail)
+    torch.cuda.synchronize()
+    assert torch.equal(out, fused_out) and torch.equal(lse, fused_lse), "same rows in the same order: same bits"
+    # oracle: the list followed by the tail rows
+    cn = np_of(cnt)
+    full = np.zeros((B, Hq, cap + 7), dtype=np.int32)
+    for b in range(B):
+        for h in range(Hq):
+            c = cn[b, h]
+            full[b, h, :c] = np_of(idx)[b, h, :c]
+            full[b, h, c:c + 7] = np.arange(tail[0], tail[1])
+    ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K), np_of(V), full, cn + 7, dtype_name(K), sm)
+    tol = 1e-5 if dtype == torch.float32 else 2e-2
+    assert np.abs(np_of(out) - ro).max() <= tol and np.abs(np_of(lse) - rl).max() <= 1e-3
+
+
+def test_buffered_interval_matches_fused_interval(oracle):
+    say("interval loop with migrated buffers against the fused-gather loop, scaled-down C4")
+    cfg = workloads.C4.scaled(name="C4_small_buf", B=2, N=4096, k=256, steps=12, P=4, heavy_per_kv_head=8)
+    data = workloads.make_layer(cfg, device=DEV)
+    K, V, W = data["K"], data["V"], data["W"]
+    Kimp = torch.zeros((cfg.B, cfg.Hkv, K.shape[2], cfg.Dimp), dtype=K.dtype, device=DEV)
+    tb.tb_project_keys(tb.make_desc(cfg.N, cfg.Hq, K=K, V=V, Kimp=Kimp), K, W, Kimp, 0, cfg.N)
+    fused = interval.IntervalDecoder(K, V, W, Kimp, cfg.Hq, cfg.k, cfg.P, cfg.radius, sm_scale=cfg.sm_scale)
+    buffered = interval.IntervalDecoder(K, V, W, Kimp.clone(), cfg.Hq, cfg.k, cfg.P, cfg.radius, sm_scale=cfg.sm_scale,
+                                        buffered=True)
+    for t in range(cfg.steps):
+        q, qi = data["q"][t].contiguous(), data["q_imp"][t].contiguous()
+        o1, l1 = fused.step(t, cfg.N + t, q, qi)
+        o1, l1 = o1.clone(), l1.clone()
+        o2, l2 = buffered.step(t, cfg.N + t, q, qi)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2) and torch.equal(l1, l2), f"step {t}"

@@ -483,3 +483,29 @@ def test_interval_driver_reduces_to_per_step_path_and_set_sizes(oracle):
             for h in range(Hq):
                 got = idx[0, h, : cnt[0, h]]
                 assert np.all(np.diff(got) > 0) and got[-1] == N_t - 1
+
+
+# --------------------------------------------------------------------------- buffer migration
+
+def test_gather_kv_rows_are_copies_in_list_order(oracle):
+    """Sec. 3.3 (Important Buffer): the migrated rows are the cache rows the list names, in list
+    order, per query head through the GQA map; attention over the buffer (identity list) equals
+    attention over the cache with the list."""
+    rng = np.random.default_rng(3)
+    B, Hq, Hkv, N, D = 2, 4, 2, 50, 8
+    K = rng.standard_normal((B, Hkv, N, D)).astype(np.float32)
+    V = rng.standard_normal((B, Hkv, N, D)).astype(np.float32)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float32)
+    idx = np.stack([np.stack([np.sort(rng.choice(N, 9, replace=False)) for _ in range(Hq)]) for _ in range(B)]).astype(np.int32)
+    cnt = rng.integers(0, 10, size=(B, Hq)).astype(np.int32)
+    Kb, Vb = oracle.gather_kv(K, V, idx, cnt, 12)
+    for b in range(B):
+        for h in range(Hq):
+            for i in range(12):
+                want = K[b, h // 2, idx[b, h, i]] if i < cnt[b, h] else np.zeros(D, np.float32)
+                assert np.array_equal(Kb[b, h, i], want)
+            assert np.array_equal(Vb[b, h, : cnt[b, h]], V[b, h // 2][idx[b, h, : cnt[b, h]]])
+    ident = np.broadcast_to(np.arange(12, dtype=np.int32), (B, Hq, 12)).copy()
+    o1, l1 = oracle.sparse_decode_attn(q, K, V, idx, cnt, "f32", 0.3)
+    o2, l2 = oracle.sparse_decode_attn(q, Kb, Vb, ident, cnt, "f32", 0.3)  # buffers: one "kv head" per query head
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
