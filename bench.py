@@ -284,6 +284,28 @@ def main():
     us_proj_bulk = timer(stage_project_bulk) if not args.kv_host else float("inf")
     us_step_eager = time_eager(step, args.steps, args.warmup) if use_graph else us_step
 
+    # query predictor of a producer layer (LN + two-layer MLP, hidden 512, 4 consumer slots; runs
+    # once per 4 layers, before the steps of its consumer layers): random weights, speed only
+    E, hidden, G = cfg.Hq * cfg.D, 512, 4
+    td = probe.K.dtype
+    pw = {
+        "h": torch.randn((cfg.B, E), device="cuda").to(td), "gamma": torch.ones(E, device="cuda").to(td),
+        "beta": torch.zeros(E, device="cuda").to(td), "W1": (torch.randn((hidden, E), device="cuda") * E ** -0.5).to(td),
+        "b1": torch.zeros(hidden, device="cuda").to(td),
+        "W2": (torch.randn((G * cfg.Hq * cfg.Dimp, hidden), device="cuda") * hidden ** -0.5).to(td),
+        "b2": torch.zeros(G * cfg.Hq * cfg.Dimp, device="cuda").to(td),
+        "z": torch.empty((cfg.B, hidden), dtype=torch.float32, device="cuda"),
+        "xln": torch.empty((cfg.B, E), dtype=torch.float32, device="cuda"),
+        "q": torch.empty((G, cfg.B, cfg.Hq, cfg.Dimp), dtype=td, device="cuda"),
+    }
+
+    def stage_predict(b):
+        tb.tb_predict_queries(pw["h"], pw["gamma"], pw["beta"], pw["W1"], pw["b1"], pw["W2"], pw["b2"], G, cfg.Hq,
+                              cfg.Dimp, pw["z"], pw["xln"], pw["q"])
+
+    us_predict = timer(stage_predict)
+    bytes_predict = (pw["W1"].numel() + pw["W2"].numel()) * cfg.elt_bytes
+
     elt = cfg.elt_bytes
     bytes_kimp = cfg.B * cfg.Hkv * cfg.N * cfg.Dimp * elt
     bytes_gather = selected_rows * 2 * cfg.D * elt
@@ -319,7 +341,10 @@ def main():
         "stages_us": {
             "score": round(us_score, 3), "select_topk": round(us_select, 3), "sparse_attn": round(us_attn, 3),
             "project_append_1row": round(us_proj, 3), "step_eager_launch": round(us_step_eager, 3),
+            "predict_queries_4slots": round(us_predict, 3),
         },
+        "predictor": {"E": E, "hidden": hidden, "slots": G, "weight_bytes": bytes_predict, "us": round(us_predict, 3),
+                      "note": "weights stay in the last-level cache between calls (8 MiB): a latency figure"},
         # the batched projection of the whole key cache (done once per window of appended tokens,
         # not per step): read K, write K_imp
         "project_bulk": {

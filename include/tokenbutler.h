@@ -144,6 +144,27 @@ tb_status tb_decode_step(const tb_cache_desc* desc, const void* q_imp, const voi
                          float sm_scale, float* scores, int64_t score_stride, int32_t* idx, int32_t* count,
                          int64_t idx_cap, float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
 
+/* Query prediction of a producer layer (Sec. 3.1 "Query prediction"): from the hidden state of
+ * the token being decoded, a LayerNorm and a two-layer MLP give one importance query per query
+ * head for each of the G consumer layers ("slots") that follow the producer:
+ *   x = LN(h) = (h - mean) / sqrt(var + ln_eps) * gamma + beta      (over E, biased variance)
+ *   z = gelu(W1 x + b1)          (exact erf form; the paper does not name the nonlinearity)
+ *   y = W2 z + b2,   q_imp[s][b][hq][j] = y[(s*Hq + hq)*Dimp + j]
+ * h: [B][E]; gamma, beta: [E]; W1: [hidden][E]; b1: [hidden]; W2: [G*Hq*Dimp][hidden];
+ * b2: [G*Hq*Dimp] -- all contiguous, all of element type `dtype`; fp32 accumulation, one rounding
+ * when q_imp is stored.  q_imp: [G][B][Hq][Dimp] of `dtype`: slot s is the [B][Hq][Dimp] array that
+ * tb_score takes for consumer layer s.  hidden_act: fp32 [B][hidden], receives z; ln_act: fp32
+ * [B][E], receives LN(h) when B > 2 (both are scratch that the caller owns; 16-byte aligned, as
+ * are h, gamma, beta, W1, W2).  E and hidden must be multiples of 8, E <= 8192, hidden <= 2048. */
+typedef struct {
+  int32_t E, hidden, G, Hq, Dimp;
+  tb_dtype dtype;
+  float ln_eps;
+} tb_predictor_desc;
+tb_status tb_predict_queries(const tb_predictor_desc* p, int32_t B, const void* h, const void* gamma,
+                             const void* beta, const void* W1, const void* b1, const void* W2, const void* b2,
+                             float* hidden_act, float* ln_act, void* q_imp, void* stream);
+
 /* Scratch size in bytes for `op` on this cache shape.  max_count is the longest list the
  * attention will see, tail included; for TB_OP_SELECT and TB_OP_DECODE_STEP it is the list
  * length the selection policy produces, lo + kk + N - hi (TB_OP_SELECT returns 0 for every

@@ -207,6 +207,33 @@ def sparse_decode_attn(q, K, V, idx, count, dtype, sm_scale: float) -> Tuple[np.
     return out, lse
 
 
+def predict_queries(h, gamma, beta, W1, b1, W2, b2, G: int, Hq: int, Dimp: int, dtype, ln_eps: float = 1e-5):
+    """Query prediction of a producer layer (Sec. 3.1 "Query prediction"): LayerNorm over the
+    model dimension, then a two-layer MLP (exact-erf GELU; the paper does not name the
+    nonlinearity), all in fp64, one rounding to the storage type at the end.
+    h [B,E]; W1 [hidden,E]; W2 [G*Hq*Dimp,hidden].  Returns (q_imp [G,B,Hq,Dimp], z [B,hidden] fp64)."""
+    import math
+
+    def f64(a):
+        a = np.asarray(a)
+        return bf16_to_f64(a) if dtype == "bf16" else a.astype(np.float64)
+
+    h, gamma, beta, W1, b1, W2, b2 = (f64(a) for a in (h, gamma, beta, W1, b1, W2, b2))
+    B, E = h.shape
+    mean = h.sum(axis=1, keepdims=True) / E
+    var = ((h - mean) ** 2).sum(axis=1, keepdims=True) / E
+    x = (h - mean) / np.sqrt(var + ln_eps) * gamma + beta
+    pre = x @ W1.T + b1
+    z = 0.5 * pre * (1.0 + np.vectorize(math.erf)(pre / math.sqrt(2.0)))
+    y = z @ W2.T + b2  # [B, G*Hq*Dimp], output row (slot, head, j) with the slot outermost
+    y = y.reshape(B, G, Hq, Dimp).transpose(1, 0, 2, 3)
+    if dtype == "bf16":
+        q = np.vectorize(round_bf16, otypes=[np.uint16])(y)
+    else:
+        q = y.astype(np.float32)
+    return np.ascontiguousarray(q), z
+
+
 def gather_kv(K, V, idx, count, buf_cap: int) -> Tuple[np.ndarray, np.ndarray]:
     """Migration of selected rows into per-query-head buffers (Sec. 3.3, the Important Buffer):
     buf[b,h,i,:] = cache[b, h // g, idx[b,h,i], :] for i < count[b,h]; the rest stays zero.

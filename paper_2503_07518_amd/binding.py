@@ -23,7 +23,7 @@ TB_OP_SELECT, TB_OP_ATTN, TB_OP_DECODE_STEP = 1, 2, 3
 
 EXPORTS = (
     "tb_project_keys", "tb_score", "tb_select_topk", "tb_expand_neighbors", "tb_sparse_decode_attn",
-    "tb_gather_kv", "tb_buffered_decode_attn", "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_status_string", "tb_version",
+    "tb_gather_kv", "tb_buffered_decode_attn", "tb_predict_queries", "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_status_string", "tb_version",
 )
 
 
@@ -40,6 +40,13 @@ class tb_cache_desc(ctypes.Structure):
         ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_n", ctypes.c_int64),
         ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_n", ctypes.c_int64),
         ("ki_stride_b", ctypes.c_int64), ("ki_stride_h", ctypes.c_int64), ("ki_stride_n", ctypes.c_int64),
+    ]
+
+
+class tb_predictor_desc(ctypes.Structure):
+    _fields_ = [
+        ("E", ctypes.c_int32), ("hidden", ctypes.c_int32), ("G", ctypes.c_int32), ("Hq", ctypes.c_int32),
+        ("Dimp", ctypes.c_int32), ("dtype", ctypes.c_int32), ("ln_eps", ctypes.c_float),
     ]
 
 
@@ -67,6 +74,7 @@ def load_library() -> ctypes.CDLL:
                                  vp, sz, vp]
     L.tb_gather_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, vp, vp, i64, vp]
     L.tb_buffered_decode_attn.argtypes = [dp, vp, vp, vp, i64, vp, i64, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
+    L.tb_predict_queries.argtypes = [ctypes.POINTER(tb_predictor_desc), i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.tb_workspace_bytes.argtypes = [i32, dp, i64]
     L.tb_workspace_bytes.restype = sz
     L.tb_workspace_init.argtypes = [vp, sz, vp]
@@ -185,6 +193,23 @@ def tb_buffered_decode_attn(desc, q, Kbuf, Vbuf, count, max_count: int, K, V, sm
                                                   sm_scale, _ptr(out), _ptr(lse), _ptr(ws),
                                                   ws.numel() * ws.element_size(), _stream(stream)),
            "tb_buffered_decode_attn")
+
+
+def tb_predict_queries(h, gamma, beta, W1, b1, W2, b2, G: int, Hq: int, Dimp: int, hidden_act, ln_act, q_imp,
+                       ln_eps: float = 1e-5, stream=None) -> None:
+    """q_imp[G][B][Hq][Dimp] = MLP(LN(h)); W1 [hidden][E], W2 [G*Hq*Dimp][hidden] (torch Linear layout)."""
+    B, E = h.shape
+    hidden = W1.shape[0]
+    for t in (h, gamma, beta, W1, b1, W2, b2, hidden_act, ln_act, q_imp):
+        assert t.is_contiguous()
+    assert W1.shape == (hidden, E) and W2.shape == (G * Hq * Dimp, hidden)
+    assert hidden_act.dtype == torch.float32 and hidden_act.shape == (B, hidden)
+    assert ln_act.dtype == torch.float32 and ln_act.shape == (B, E)
+    assert q_imp.shape == (G, B, Hq, Dimp) and q_imp.dtype == h.dtype
+    p = tb_predictor_desc(E, hidden, G, Hq, Dimp, _dtype_code(h), ln_eps)
+    _check(load_library().tb_predict_queries(ctypes.byref(p), B, _ptr(h), _ptr(gamma), _ptr(beta), _ptr(W1), _ptr(b1),
+                                             _ptr(W2), _ptr(b2), _ptr(hidden_act), _ptr(ln_act), _ptr(q_imp), _stream(stream)),
+           "tb_predict_queries")
 
 
 def tb_expand_neighbors(B: int, Hq: int, N: int, radius: int, mode: int, idx_in, count_in, idx_out, count_out,

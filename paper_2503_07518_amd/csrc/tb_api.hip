@@ -275,6 +275,25 @@ tb_status tb_buffered_decode_attn(const tb_cache_desc* d, const void* q, const v
   return launch_attn(L, static_cast<hipStream_t>(stream));
 }
 
+tb_status tb_predict_queries(const tb_predictor_desc* p, int32_t B, const void* h, const void* gamma,
+                             const void* beta, const void* W1, const void* b1, const void* W2, const void* b2,
+                             float* hidden_act, float* ln_act, void* q_imp, void* stream) {
+  if (!p || B < 0) return TB_ERR_INVALID_ARG;
+  if (p->E <= 0 || p->hidden <= 0 || p->G <= 0 || p->Hq <= 0 || p->Dimp <= 0) return TB_ERR_INVALID_ARG;
+  if (p->dtype != TB_F32 && p->dtype != TB_BF16) return TB_ERR_INVALID_ARG;
+  if (!(p->ln_eps >= 0.f)) return TB_ERR_INVALID_ARG;
+  if (!h || !gamma || !beta || !W1 || !b1 || !W2 || !b2 || !hidden_act || !ln_act || !q_imp)
+    return TB_ERR_INVALID_ARG;
+  if (p->E % 8 || p->hidden % 8 || p->E > 8192 || p->hidden > 2048 || B > 65535) return TB_ERR_UNSUPPORTED;
+  if (static_cast<int64_t>(p->G) * p->Hq * p->Dimp > (int64_t{1} << 24)) return TB_ERR_UNSUPPORTED;
+  if (!aligned16(W1) || !aligned16(W2) || !aligned16(h) || !aligned16(gamma) || !aligned16(beta) ||
+      !aligned16(ln_act))
+    return TB_ERR_UNSUPPORTED;
+  PredictLaunch L{p->dtype, B, p->E, p->hidden, p->G, p->Hq, p->Dimp, p->ln_eps, h, gamma, beta, W1, b1, W2, b2,
+                  hidden_act, ln_act, q_imp};
+  return launch_predict(L, static_cast<hipStream_t>(stream));
+}
+
 tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* Kimp, float score_scale,
                          const void* q, const void* K, const void* V, int32_t k, int32_t sink, int32_t window,
                          float sm_scale, float* scores, int64_t score_stride, int32_t* idx, int32_t* count,

@@ -113,6 +113,18 @@ tb_status launch_gather(const GatherLaunch& a, hipStream_t st);
 int attn_tile_rows_per_wg(int dtype, int D);
 tb_status launch_attn(const AttnLaunch& a, hipStream_t st);
 
+// Query predictor of a producer layer (LN + two-layer MLP), see tb_predict.hip.
+struct PredictLaunch {
+  int dtype;
+  int32_t B, E, hidden, G, Hq, Dimp;
+  float eps;
+  const void *h, *gamma, *beta, *W1, *b1, *W2, *b2;
+  float* z;
+  float* xln;
+  void* q_imp;
+};
+tb_status launch_predict(const PredictLaunch& a, hipStream_t st);
+
 tb_status launch_project(const tb_cache_desc* d, const void* K, const void* W, int32_t Hw, void* Kimp,
                          int64_t n_begin, int64_t n_end, hipStream_t st);
 

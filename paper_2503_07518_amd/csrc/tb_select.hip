@@ -193,8 +193,10 @@ constexpr int kStreamBatch = 8;  // tiles in flight per wave while streaming
 
 constexpr int kMaxLevels = 4;  // bracketed level (possibly repeated once over all bins) + up to 2 levels of low bits
 
-template <int NT>  // NT > 0: the wave's tiles are cached in registers (NT >= tiles per wave);
-                   // NT == 0: streamed again in every phase
+// STAGE 0: the whole selection of a row; 1: stage A of a two-stage selection (a piece of a row);
+// 2: stage B (the row is the candidate array of stage A)
+template <int NT, int STAGE>  // NT > 0: the wave's tiles are cached in registers (NT >= tiles per wave);
+                              // NT == 0: streamed again in every phase
 __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void select_kernel(SelectArgs a) {
   __shared__ uint32_t s_hist[2][kHistBins];  // alternating: one in use, the other being cleared
   __shared__ __attribute__((aligned(16))) Found s_found[kMaxLevels + 1];
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   int64_t N = a.N;
   int64_t row_off = 0;      // stage A: where this piece starts in the row
   int64_t cand_off = 0;     // stage A: kept keys of the pieces before this one
-  if (a.chunks > 1) {
+  if constexpr (STAGE == 1) {
     const int c = blockIdx.x % a.chunks;
     u = blockIdx.x / a.chunks;
     for (int cc = 0; cc <= c; ++cc) {
@@ -265,7 +267,7 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   int32_t* sel_out;
   float* cand = nullptr;
   const int32_t* remap = nullptr;
-  if (a.chunks > 1) {
+  if constexpr (STAGE == 1) {
     sel_out = out + cand_off;
     cand = a.cand_score + static_cast<int64_t>(u) * a.idx_cap + cand_off;
   } else {
@@ -274,7 +276,7 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
     for (int64_t n = e_hi + tid; n < a.emit_N; n += kSelThreads) out[e_lo + kk + (n - e_hi)] = static_cast<int32_t>(n);
     if (tid == 0) a.count[u] = static_cast<int32_t>(e_lo + kk + (a.emit_N - e_hi));
     sel_out = out + e_lo;
-    if (a.remap) remap = a.remap + static_cast<int64_t>(u) * a.score_stride;
+    if constexpr (STAGE == 2) remap = a.remap + static_cast<int64_t>(u) * a.score_stride;
   }
   if (kk == 0) return;
 
@@ -546,8 +548,12 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   // Pass B: position of a kept key = (#greater before it) + min(#equal before it, r_eq)
   auto emit = [&](uint32_t pos, int32_t n, uint32_t key) {
     if (pos < static_cast<uint32_t>(kk)) {
-      sel_out[pos] = remap ? remap[n] : static_cast<int32_t>(row_off) + n;
-      if (cand) cand[pos] = key_to_score(key);
+      if constexpr (STAGE == 0) sel_out[pos] = n;
+      if constexpr (STAGE == 1) {
+        sel_out[pos] = static_cast<int32_t>(row_off) + n;
+        cand[pos] = key_to_score(key);
+      }
+      if constexpr (STAGE == 2) sel_out[pos] = remap[n];
     }
   };
   for_each_tile([&](int j, const uint32_t(&k4)[4]) {
@@ -594,6 +600,7 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
 
 namespace {
 
+template <int STAGE>
 tb_status launch_one(const SelectArgs& a, int64_t workgroups, int64_t row_len, hipStream_t st) {
   SelectArgs b = a;
   const int32_t tiles = static_cast<int32_t>((row_len + kTileElts - 1) / kTileElts);  // per wave
@@ -601,17 +608,17 @@ tb_status launch_one(const SelectArgs& a, int64_t workgroups, int64_t row_len, h
   dim3 grid(static_cast<unsigned>(workgroups));
   dim3 block(kSelThreads);
   if (tiles <= 1)
-    hipLaunchKernelGGL(select_kernel<1>, grid, block, 0, st, b);
+    hipLaunchKernelGGL((select_kernel<1, STAGE>), grid, block, 0, st, b);
   else if (tiles <= 2)
-    hipLaunchKernelGGL(select_kernel<2>, grid, block, 0, st, b);
+    hipLaunchKernelGGL((select_kernel<2, STAGE>), grid, block, 0, st, b);
   else if (tiles <= 4)
-    hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, st, b);
+    hipLaunchKernelGGL((select_kernel<4, STAGE>), grid, block, 0, st, b);
   else if (tiles <= 8)
-    hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, st, b);
+    hipLaunchKernelGGL((select_kernel<8, STAGE>), grid, block, 0, st, b);
   else if (tiles <= 16)
-    hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, st, b);
+    hipLaunchKernelGGL((select_kernel<16, STAGE>), grid, block, 0, st, b);
   else
-    hipLaunchKernelGGL(select_kernel<0>, grid, block, 0, st, b);
+    hipLaunchKernelGGL((select_kernel<0, STAGE>), grid, block, 0, st, b);
   return hip_status(hipGetLastError());
 }
 
@@ -638,7 +645,7 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   a.emit_N = L.N;
   const SelectPlan plan = select_plan(L.units, L.N, L.kk);
   if (plan.chunks <= 1 || !L.scratch || L.scratch_bytes < select_scratch_bytes(L.units, plan))
-    return launch_one(a, L.units, L.N, st);
+    return launch_one<0>(a, L.units, L.N, st);
 
   // stage A: every piece keeps its own top-kk; positions and scores land in the scratch arrays
   int32_t* cand_idx = static_cast<int32_t*>(L.scratch);
@@ -650,7 +657,7 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   sa.idx_cap = plan.cand_stride;
   sa.cand_score = cand_score;
   sa.count = nullptr;
-  const tb_status rc = launch_one(sa, L.units * plan.chunks, plan.chunk_len, st);
+  const tb_status rc = launch_one<1>(sa, L.units * plan.chunks, plan.chunk_len, st);
   if (rc != TB_OK) return rc;
   // stage B: the kk largest among what the pieces kept (the same host arithmetic as the kernel's)
   int64_t n_cand = 0;
@@ -670,7 +677,7 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   sb.lo = 0;
   sb.hi = static_cast<int32_t>(n_cand);
   sb.remap = cand_idx;
-  return launch_one(sb, L.units, n_cand, st);
+  return launch_one<2>(sb, L.units, n_cand, st);
 }
 
 }  // namespace tb

@@ -509,3 +509,44 @@ def test_gather_kv_rows_are_copies_in_list_order(oracle):
     o1, l1 = oracle.sparse_decode_attn(q, K, V, idx, cnt, "f32", 0.3)
     o2, l2 = oracle.sparse_decode_attn(q, Kb, Vb, ident, cnt, "f32", 0.3)  # buffers: one "kv head" per query head
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+# --------------------------------------------------------------------------- query predictor
+
+def test_predict_queries_against_library_layers_and_closed_forms(oracle):
+    """Sec. 3.1 "Query prediction": LN + two-layer MLP.  Pinned to torch's own layer_norm /
+    linear / gelu in fp64, to the slot-outermost output layout, and to closed forms (a constant
+    hidden state normalises to beta; zero first-layer weights give gelu(b1) for every row)."""
+    import torch
+    import torch.nn.functional as F
+
+    rng = np.random.default_rng(7)
+    B, E, hidden, G, Hq, Dimp = 3, 64, 24, 2, 4, 8
+    h = rng.standard_normal((B, E)).astype(np.float32) * 3 + 1
+    gamma = rng.standard_normal(E).astype(np.float32)
+    beta = rng.standard_normal(E).astype(np.float32)
+    W1 = rng.standard_normal((hidden, E)).astype(np.float32) / 8
+    b1 = rng.standard_normal(hidden).astype(np.float32)
+    W2 = rng.standard_normal((G * Hq * Dimp, hidden)).astype(np.float32) / 5
+    b2 = rng.standard_normal(G * Hq * Dimp).astype(np.float32)
+    q, z = oracle.predict_queries(h, gamma, beta, W1, b1, W2, b2, G, Hq, Dimp, "f32")
+    t = lambda a: torch.from_numpy(a).double()
+    x = F.layer_norm(t(h), (E,), t(gamma), t(beta), 1e-5)
+    zt = F.gelu(F.linear(x, t(W1), t(b1)))
+    yt = F.linear(zt, t(W2), t(b2)).reshape(B, G, Hq, Dimp).permute(1, 0, 2, 3)
+    assert np.allclose(z, zt.numpy(), rtol=1e-12, atol=1e-12)
+    assert np.allclose(q, yt.numpy().astype(np.float32), rtol=1e-6, atol=1e-6)
+    # layout: output row (s*Hq + hq)*Dimp + j lands in q[s, b, hq, j]
+    W2m = np.zeros_like(W2)
+    b2m = np.arange(G * Hq * Dimp, dtype=np.float32)
+    qm, _ = oracle.predict_queries(h, gamma, beta, W1, b1, W2m, b2m, G, Hq, Dimp, "f32")
+    assert np.array_equal(qm[1, 2, 3], (1 * Hq + 3) * Dimp + np.arange(Dimp, dtype=np.float32))
+    # constant hidden state: variance 0, LN gives beta exactly
+    hc = np.full((1, E), 2.5, dtype=np.float32)
+    _, zc = oracle.predict_queries(hc, gamma, beta, W1, b1, W2, b2, G, Hq, Dimp, "f32")
+    pre = beta.astype(np.float64) @ W1.astype(np.float64).T + b1
+    assert np.allclose(zc[0], 0.5 * pre * (1 + np.array([math.erf(v / math.sqrt(2)) for v in pre])), atol=1e-12)
+    # bf16 storage: the stored value is the nearest bf16 of the fp64 result
+    qb, _ = oracle.predict_queries(*(oracle.to_numpy(torch.from_numpy(a).bfloat16()) for a in (h, gamma, beta, W1, b1, W2, b2)),
+                                   G, Hq, Dimp, "bf16")
+    assert qb.dtype == np.uint16 and qb.shape == (G, B, Hq, Dimp)
