@@ -344,7 +344,7 @@ def main():
             "predict_queries_4slots": round(us_predict, 3),
         },
         "predictor": {"E": E, "hidden": hidden, "slots": G, "weight_bytes": bytes_predict, "us": round(us_predict, 3),
-                      "note": "weights stay in the last-level cache between calls (8 MiB): a latency figure"},
+                      "note": "two launches that read 8 MiB of weights: a latency figure"},
         # the batched projection of the whole key cache (done once per window of appended tokens,
         # not per step): read K, write K_imp
         "project_bulk": {
