@@ -68,6 +68,11 @@ def test_workspace_sizes(tb):
     assert tb.tb_workspace_bytes(99, d, 0) == 0
     assert tb.tb_workspace_bytes(tb.TB_OP_ATTN, desc(tb, D=96), 10) == 0
     assert tb.tb_workspace_bytes(tb.TB_OP_ATTN, d, -1) == 0
+    # long rows on few heads are selected in two stages and need room for the candidates
+    long_row = desc(tb, N=1 << 20)
+    need = tb.tb_workspace_bytes(tb.TB_OP_SELECT, long_row, 8192)
+    assert need >= 8 * 8 * 8192 * 8 and tb.tb_workspace_bytes(tb.TB_OP_DECODE_STEP, long_row, 8192) >= need
+    assert tb.tb_workspace_bytes(tb.TB_OP_SELECT, long_row, 0) == 0
 
 
 def test_rejects_bad_arguments_without_launching(tb):
@@ -112,6 +117,25 @@ def test_rejects_bad_arguments_without_launching(tb):
     # fused step inherits all of the above
     assert L.tb_decode_step(r(d), P, P, 1.0, P, P, P, 10, 0, 0, 1.0, P, 1000, P, P, 9, P, NULL, P, 1 << 24, None) == tb.TB_ERR_INVALID_ARG
     assert L.tb_decode_step(r(d), P, P, 1.0, P, P, P, 10, 0, 0, 1.0, P, 1000, P, P, 10, P, NULL, P, 64, None) == tb.TB_ERR_WORKSPACE
+    # buffer migration and buffered attention: capacities, null buffers, workspace
+    assert L.tb_gather_kv(r(d), P, P, P, P, 100, 101, P, P, 200, None) == tb.TB_ERR_INVALID_ARG  # max_count > idx_cap
+    assert L.tb_gather_kv(r(d), P, P, P, P, 100, 100, P, P, 99, None) == tb.TB_ERR_INVALID_ARG   # buffer too small
+    assert L.tb_gather_kv(r(d), P, P, P, P, 100, 100, NULL, P, 100, None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_gather_kv(r(d), P, P, P, P, 100, 100, ctypes.c_void_p(0x10008), P, 100, None) == tb.TB_ERR_UNSUPPORTED
+    assert L.tb_buffered_decode_attn(r(d), P, NULL, P, 100, P, 100, P, P, 0, 0, 1.0, P, NULL, P, 1 << 24, None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_buffered_decode_attn(r(d), P, P, P, 100, P, 101, P, P, 0, 0, 1.0, P, NULL, P, 1 << 24, None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_buffered_decode_attn(r(d), P, P, P, 100, P, 100, P, P, 0, 1001, 1.0, P, NULL, P, 1 << 24, None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_buffered_decode_attn(r(d), P, P, P, 100, P, 100, P, P, 0, 0, 1.0, P, NULL, P, 64, None) == tb.TB_ERR_WORKSPACE
+    # query predictor: shapes, null pointers, sizes outside the supported range
+    pd = tb.tb_predictor_desc(4096, 512, 4, 32, 32, tb.TB_BF16, 1e-5)
+    args = (P, P, P, P, P, P, P, P, P, P)
+    assert L.tb_predict_queries(r(pd), 1, NULL, *args[1:], None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_predict_queries(r(pd), -1, *args, None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_predict_queries(r(tb.tb_predictor_desc(4100, 512, 4, 32, 32, tb.TB_BF16, 1e-5)), 1, *args, None) == tb.TB_ERR_UNSUPPORTED
+    assert L.tb_predict_queries(r(tb.tb_predictor_desc(16384, 512, 4, 32, 32, tb.TB_BF16, 1e-5)), 1, *args, None) == tb.TB_ERR_UNSUPPORTED
+    assert L.tb_predict_queries(r(tb.tb_predictor_desc(4096, 512, 0, 32, 32, tb.TB_BF16, 1e-5)), 1, *args, None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_predict_queries(r(tb.tb_predictor_desc(4096, 512, 4, 32, 32, 7, 1e-5)), 1, *args, None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_predict_queries(r(pd), 0, *args, None) == tb.TB_OK  # empty batch: no-op
     # workspace init
     assert L.tb_workspace_init(NULL, 16, None) == tb.TB_ERR_INVALID_ARG
     assert L.tb_workspace_init(P, 6, None) == tb.TB_ERR_INVALID_ARG
