@@ -216,6 +216,15 @@ def main():
     cal_dst = torch.empty_like(cal_src)
     for _ in range(3):
         cal_dst.copy_(cal_src)
+    # the same copy timed: what a plain streaming kernel reaches on this machine, next to the 8 TB/s of the data sheet
+    torch.cuda.synchronize()
+    ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ce0.record()
+    for _ in range(5):
+        cal_dst.copy_(cal_src)
+    ce1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * (256 << 20) / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
     del cal_src, cal_dst
 
     for b in bufs:  # first touch, also fills idx/cnt for the per-stage timings
@@ -358,6 +367,7 @@ def main():
             "algorithmic_bytes": bytes_gather, "us": round(us_attn, 3),
             "traffic": MEASURED_ATTN_TRAFFIC.get(cfg.name),
         },
+        "device_copy_256MiB_GBps": round(copy_gbps, 1),
         "timed_wall_s": round(wall_s, 3),
     }
 
