@@ -121,12 +121,6 @@ __device__ inline uint32_t wave_incl_scan_u32(uint32_t v) {
   return v;
 }
 
-// Number of set bits of a wave-wide ballot in the lanes below this one.
-__device__ inline uint32_t lanes_below(unsigned long long ballot) {
-  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(ballot >> 32),
-                                   __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(ballot), 0u));
-}
-
 // Sum over aligned groups of LANES adjacent lanes (LANES = 1..32, a power of two); every lane
 // of a group receives the group's total.  The exchanges inside a row of 16 lanes are DPP moves
 // (swap neighbours, swap pairs, mirror the half row, mirror the row) and stay in the VALU;
@@ -145,13 +139,6 @@ __device__ inline float group_allreduce_sum(float s) {
   if (LANES >= 16) s += dpp(s, std::integral_constant<int, kRowMirror>{});
   if (LANES >= 32) s += __shfl_xor(s, 16, kWave);
   return s;
-}
-
-template <typename T>
-__device__ inline T wave_sum(T v) {
-#pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
 }
 
 // Exclusive prefix sum over the threads of a block of NWAVES waves (thread order).
@@ -176,27 +163,6 @@ __device__ inline T block_excl_scan(T v, T* s_tmp, T& total) {
   __syncthreads();
   const T base = s_tmp[wave];
   total = s_tmp[NWAVES];
-  __syncthreads();
-  return base + incl - v;
-}
-
-// Same for 32-bit counts, with the DPP wave scan; every thread adds up the totals of the
-// waves before its own (NWAVES <= 16 broadcast reads) instead of waiting for one thread.
-template <int NWAVES>
-__device__ inline uint32_t block_excl_scan_u32(uint32_t v, uint32_t* s_tmp, uint32_t& total) {
-  const int lane = lane_id();
-  const int wave = threadIdx.x / kWave;
-  const uint32_t incl = wave_incl_scan_u32(v);
-  if (lane == kWave - 1) s_tmp[wave] = incl;
-  __syncthreads();
-  uint32_t base = 0, all = 0;
-#pragma unroll
-  for (int w = 0; w < NWAVES; ++w) {
-    const uint32_t t = s_tmp[w];
-    base += (w < wave) ? t : 0u;
-    all += t;
-  }
-  total = all;
   __syncthreads();
   return base + incl - v;
 }
