@@ -31,22 +31,21 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
   return p;
 }
 
-SelectPlan select_plan(int64_t units, int64_t N, int64_t kk) {
+SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk) {
   SelectPlan p{1, 0, 0};
-  if (units <= 0 || kk <= 0 || N < 131072) return p;
-  int64_t s = 256 / units;                      // pieces per head that the 256 compute units can take
-  if (s > N / 32768) s = N / 32768;             // a piece is worth a workgroup from 32K scores on
-  if (s > 16) s = 16;
-  if (s < 2) return p;
-  int64_t len = (N + s - 1) / s;
-  len = (len + 4095) / 4096 * 4096;
-  s = (N + len - 1) / len;
-  if (s < 2) return p;
-  const int64_t per_piece = kk < len ? kk : len;
-  if (s * per_piece > N / 2) return p;           // the second stage would be as long as the row
-  p.chunks = static_cast<int>(s);
-  p.chunk_len = len;
-  p.cand_stride = (s * per_piece + 3) / 4 * 4;
+  // worth it when the row is long and the budget a small share of the candidates (the kept keys
+  // are then a small share of the row as well)
+  if (units <= 0 || kk <= 0 || N < 131072 || kk * 8 > candidates) return p;
+  int64_t len = 32768;
+  if (units * ((N + len - 1) / len) > 512) len = 65536;   // at most two rounds of workgroups on 256 compute units
+  if ((N + len - 1) / len > 16) len = ((N + 15) / 16 + 4095) / 4096 * 4096;
+  if (len > 65536) return p;                              // a piece has to fit the registers of its workgroup
+  const int64_t pieces = (N + len - 1) / len;
+  if (pieces < 2) return p;
+  p.pieces = static_cast<int>(pieces);
+  p.piece_len = len;
+  const int64_t cap = 2 * kk + 4096;                      // the budget, the bracket's slack, a coarse top bin
+  p.cap = ((cap < len ? cap : len) + 3) / 4 * 4;
   return p;
 }
 
@@ -338,8 +337,9 @@ size_t tb_workspace_bytes(int32_t op, const tb_cache_desc* d, int64_t max_count)
   if (check_desc(d) != TB_OK || max_count < 0) return 0;
   const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
   // two-stage selection of long rows (none for most shapes): max_count bounds the budget
-  const int64_t kk_bound = max_count < d->N ? max_count : d->N;
-  const size_t sel = select_scratch_bytes(units, select_plan(units, d->N, kk_bound));
+  // (sized for the largest budget that still takes the two-stage path on this row length)
+  int64_t kk_bound = max_count < d->N / 8 ? max_count : d->N / 8;
+  const size_t sel = select_scratch_bytes(units, select_plan(units, d->N, d->N, kk_bound));
   const size_t sel_total = sel ? ws_layout(units, d->D, 1).part_off + align_up(sel, 256) : 0;
   if (op == TB_OP_SELECT) return sel_total;
   if (op == TB_OP_ATTN || op == TB_OP_DECODE_STEP) {

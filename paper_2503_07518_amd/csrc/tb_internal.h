@@ -48,19 +48,19 @@ struct ScoreLaunch {
 };
 tb_status launch_score(const ScoreLaunch& a, hipStream_t st);
 
-// Long rows on few heads are selected in two stages so that more than one compute unit works
-// on a head: the row is cut into `chunks` pieces, each piece keeps its own top-kk (stage A, one
-// workgroup per piece), and the final kk are selected among the kept ones (stage B).
-// chunks == 1: one workgroup per row, no scratch.
+// Long rows are selected in two stages so that several compute units work on a head: the row
+// is cut into `pieces` pieces, every piece keeps the candidates that a sample of the row puts
+// at or above the k-th largest (stage A, one workgroup per piece), and the final kk are
+// selected among the kept ones (stage B).  pieces == 1: one workgroup per row, no scratch.
 struct SelectPlan {
-  int chunks;
-  int64_t chunk_len;    // scores per piece (a multiple of the 4096-score workgroup tile)
-  int64_t cand_stride;  // capacity of a head's candidate arrays (a multiple of 4)
+  int pieces;
+  int64_t piece_len;  // scores per piece (a multiple of the 4096-score workgroup tile, <= 65536)
+  int64_t cap;        // kept keys a piece has room for (a multiple of 4)
 };
-SelectPlan select_plan(int64_t units, int64_t N, int64_t kk);
-// candidate indices int32 [units][cand_stride] followed by candidate scores fp32 [units][cand_stride]
+SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk);
+// kept positions int32 and scores fp32, [units][pieces][cap] each, then int32 counts [units][pieces]
 inline size_t select_scratch_bytes(int64_t units, const SelectPlan& p) {
-  return p.chunks > 1 ? static_cast<size_t>(units) * p.cand_stride * 8 : 0;
+  return p.pieces > 1 ? static_cast<size_t>(units) * p.pieces * (p.cap * 8 + 4) : 0;
 }
 
 struct SelectLaunch {

@@ -52,17 +52,20 @@ struct SelectArgs {
   int32_t* count;
   int64_t idx_cap;
   int32_t tiles_per_wave;
-  // Two-stage selection of long rows.  Stage A (chunks > 1): workgroup (u, c) selects inside
-  // piece c of row u and writes the kept positions (as positions of the whole row) and their
-  // scores densely behind those of the pieces before it; no sink/window ranges, no count.
-  // Stage B (remap != NULL): the row is the candidate array of stage A; a kept position p is
-  // written as remap[p], and the sink/window ranges and the count are those of the original row.
-  int32_t chunks;
-  int64_t chunk_len;
+  // Two-stage selection of long rows.  Stage A (prefilter_kernel) cuts the row into `pieces`
+  // pieces and keeps, per piece, the candidates whose key is not below a threshold that a
+  // sample of the whole row puts safely under the kk-th largest key: positions (of the whole
+  // row) and scores go to cand_idx / cand_score [unit][piece][cap] in position order, the
+  // number found to piece_count[unit][piece] (it may exceed cap: then the piece overflowed).
+  // Stage B (stage_b_kernel) selects the kk largest among the kept ones, read as one row
+  // through the table of piece counts; if the pieces hold fewer than kk keys together or one
+  // overflowed -- the sample misled -- it selects on the original row instead.
+  int32_t pieces;
+  int64_t piece_len;
+  int64_t cap;
+  int32_t* cand_idx;
   float* cand_score;
-  const int32_t* remap;
-  int32_t emit_lo, emit_hi;  // the original row's candidate range (== lo, hi without stages)
-  int64_t emit_N;
+  int32_t* piece_count;
 };
 
 // A score whose key is `key` (the inverse of score_key up to the folding of NaN and -0).
@@ -193,11 +196,14 @@ constexpr int kStreamBatch = 8;  // tiles in flight per wave while streaming
 
 constexpr int kMaxLevels = 4;  // bracketed level (possibly repeated once over all bins) + up to 2 levels of low bits
 
-// STAGE 0: the whole selection of a row; 1: stage A of a two-stage selection (a piece of a row);
-// 2: stage B (the row is the candidate array of stage A)
-template <int NT, int STAGE>  // NT > 0: the wave's tiles are cached in registers (NT >= tiles per wave);
-                              // NT == 0: streamed again in every phase
-__global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void select_kernel(SelectArgs a) {
+constexpr int kMaxPieces = 16;
+
+// STAGE 0: the selection of a row of scores; 2: stage B of a two-stage selection (the row is
+// what the pieces of stage A kept: `n_rows` keys read through the piece table in LDS).
+// NT > 0: the wave's tiles are cached in registers (NT >= tiles per wave); NT == 0: the row is
+// streamed again in every phase.
+template <int NT, int STAGE>
+__device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t* s_ptab) {
   __shared__ uint32_t s_hist[2][kHistBins];  // alternating: one in use, the other being cleared
   __shared__ __attribute__((aligned(16))) Found s_found[kMaxLevels + 1];
   __shared__ uint32_t s_part[2][kSelWaves];
@@ -215,76 +221,80 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = tid / kWave;
-  int u = blockIdx.x;
-  int lo = a.lo, hi = a.hi, kk = a.kk;
-  int64_t N = a.N;
-  int64_t row_off = 0;      // stage A: where this piece starts in the row
-  int64_t cand_off = 0;     // stage A: kept keys of the pieces before this one
-  if constexpr (STAGE == 1) {
-    const int c = blockIdx.x % a.chunks;
-    u = blockIdx.x / a.chunks;
-    for (int cc = 0; cc <= c; ++cc) {
-      const int64_t base = cc * a.chunk_len;
-      int64_t n_c = a.N - base;
-      n_c = n_c < 0 ? 0 : (n_c > a.chunk_len ? a.chunk_len : n_c);
-      int64_t lo_c = a.lo - base, hi_c = a.hi - base;
-      lo_c = lo_c < 0 ? 0 : (lo_c > n_c ? n_c : lo_c);
-      hi_c = hi_c < lo_c ? lo_c : (hi_c > n_c ? n_c : hi_c);
-      const int64_t kk_c = a.kk < hi_c - lo_c ? a.kk : hi_c - lo_c;
-      if (cc < c) {
-        cand_off += kk_c;
-      } else {
-        row_off = base;
-        N = n_c;
-        lo = static_cast<int>(lo_c);
-        hi = static_cast<int>(hi_c);
-        kk = static_cast<int>(kk_c);
-      }
-    }
-  }
-  const float* s = a.scores + static_cast<int64_t>(u) * a.score_stride + row_off;
+  const int u = blockIdx.x;
+  const int kk = a.kk;
+  // stage B: the row is the concatenation of the pieces' kept keys, every piece padded to a
+  // multiple of 4 (s_ptab[c] = where piece c starts in it, s_ptab[kMaxPieces] = its length,
+  // s_ptab[kMaxPieces + 1 + c] = keys in piece c); every key of it is a candidate
+  const int64_t N = STAGE == 2 ? static_cast<int64_t>(s_ptab[kMaxPieces]) : a.N;
+  const int lo = STAGE == 2 ? 0 : a.lo, hi = STAGE == 2 ? static_cast<int>(N) : a.hi;
+  const float* s = STAGE == 2 ? a.cand_score + static_cast<int64_t>(u) * a.pieces * a.cap
+                              : a.scores + static_cast<int64_t>(u) * a.score_stride;
   int32_t* out = a.idx + static_cast<int64_t>(u) * a.idx_cap;
-  const int tpw = (NT > 0) ? NT : a.tiles_per_wave;
+  // stage B: as many tiles per wave as the row needs (its length is not known at launch)
+  const int tpw_b = static_cast<int>((N + kTileElts - 1) / kTileElts);
+  const int tpw = (NT > 0) ? (STAGE == 2 ? (tpw_b < 1 ? 1 : (tpw_b < NT ? tpw_b : NT)) : NT) : a.tiles_per_wave;
   const int64_t wbase = static_cast<int64_t>(wave) * tpw * kWaveTile + lane * 4;
   const bool refine = kk > 0 && kk < hi - lo;
 
   TB_MARK(0);
   const int64_t last4 = N > 0 ? ((N - 1) & ~int64_t{3}) : 0;  // the vector that holds the last score
+  // stage B: where position n (a multiple of 4) of the row lies in the [piece][cap] arrays, and
+  // how many of the four keys from there on are real (the rest is padding)
+  auto locate = [&](int64_t n, int& valid) -> int64_t {
+    int c = 0;
+#pragma unroll
+    for (int cc = 1; cc < kMaxPieces; ++cc) c += (cc < a.pieces && static_cast<int64_t>(s_ptab[cc]) <= n) ? 1 : 0;
+    const int64_t off = n - s_ptab[c];
+    valid = static_cast<int>(s_ptab[kMaxPieces + 1 + c]) - static_cast<int>(off);
+    return c * a.cap + off;
+  };
   uint32_t keys[NT > 0 ? NT : 1][4];
   if (NT > 0 && kk > 0) {
     float4 raw[NT > 0 ? NT : 1];  // every load of the thread is issued before the first is used
+    if constexpr (STAGE == 2) {
+      int valid[NT > 0 ? NT : 1];
 #pragma unroll
-    for (int j = 0; j < NT; ++j) raw[j] = load_scores4(s, last4, wbase + j * kWaveTile);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int j = 0; j < NT; ++j) {
+        const int64_t n0 = wbase + j * kWaveTile;
+        valid[j] = 0;
+        const int64_t phys = (j < tpw && n0 < N) ? locate(n0, valid[j]) : 0;
+        raw[j] = *reinterpret_cast<const float4*>(s + phys);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int j = 0; j < NT; ++j) keys_of4(raw[j], lo, hi, wbase + j * kWaveTile, keys[j]);
+      for (int j = 0; j < NT; ++j) {
+        const float v[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) keys[j][c] = c < valid[j] ? score_key(v[c]) : 0u;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < NT; ++j) raw[j] = load_scores4(s, last4, wbase + j * kWaveTile);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < NT; ++j) keys_of4(raw[j], lo, hi, wbase + j * kWaveTile, keys[j]);
+    }
   }
   for (int i = tid; i < 2 * kHistBins; i += kSelThreads) (&s_hist[0][0])[i] = 0;
   if (tid < (kMaxLevels + 1) * 8) reinterpret_cast<uint32_t*>(s_found)[tid] = 0;
   if (tid == 0) s_nlist = 0;
 
   // always-kept ranges: sink prefix [0, lo) and local window [hi, N) of the original row
-  int32_t* sel_out;
-  float* cand = nullptr;
-  const int32_t* remap = nullptr;
-  if constexpr (STAGE == 1) {
-    sel_out = out + cand_off;
-    cand = a.cand_score + static_cast<int64_t>(u) * a.idx_cap + cand_off;
-  } else {
-    const int e_lo = a.emit_lo, e_hi = a.emit_hi;
-    for (int64_t n = tid; n < e_lo; n += kSelThreads) out[n] = static_cast<int32_t>(n);
-    for (int64_t n = e_hi + tid; n < a.emit_N; n += kSelThreads) out[e_lo + kk + (n - e_hi)] = static_cast<int32_t>(n);
-    if (tid == 0) a.count[u] = static_cast<int32_t>(e_lo + kk + (a.emit_N - e_hi));
-    sel_out = out + e_lo;
-    if constexpr (STAGE == 2) remap = a.remap + static_cast<int64_t>(u) * a.score_stride;
-  }
+  // (in stage B these are the ranges of the original row: a.lo, a.hi, a.N)
+  for (int64_t n = tid; n < a.lo; n += kSelThreads) out[n] = static_cast<int32_t>(n);
+  for (int64_t n = a.hi + tid; n < a.N; n += kSelThreads) out[a.lo + kk + (n - a.hi)] = static_cast<int32_t>(n);
+  if (tid == 0) a.count[u] = static_cast<int32_t>(a.lo + kk + (a.N - a.hi));
+  int32_t* sel_out = out + a.lo;
+  const int32_t* remap = STAGE == 2 ? a.cand_idx + static_cast<int64_t>(u) * a.pieces * a.cap : nullptr;
   if (kk == 0) return;
 
   // visit every tile of this wave's span: body(j, keys of the tile)
   auto for_each_tile = [&](auto&& body) {
     if constexpr (NT > 0) {
 #pragma unroll
-      for (int j = 0; j < NT; ++j) body(j, keys[j]);
+      for (int j = 0; j < NT; ++j)
+        if (STAGE != 2 || j < tpw) body(j, keys[j]);
     } else {
       // streamed: the loads of kStreamBatch tiles are issued before the first tile is used (one
       // load per iteration would leave a wave with 1 KiB in flight and the pass latency-bound)
@@ -325,7 +335,7 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
     for (int i = 0; i < kSamples; ++i) {
       uint32_t ks;
       if constexpr (NT > 0) {
-        ks = keys[(i * NT) / kSamples][0];
+        ks = keys[STAGE == 2 ? i : (i * NT) / kSamples][0];  // (stage B: the row may end after a few tiles)
       } else {
         uint32_t k4[4];
         keys_of4(sraw[i], lo, hi, wbase + static_cast<int64_t>((i * tpw) / kSamples) * kWaveTile, k4);
@@ -546,14 +556,11 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   uint32_t base_eq = wave_entries_scan(s_weq, unused_total);
 
   // Pass B: position of a kept key = (#greater before it) + min(#equal before it, r_eq)
-  auto emit = [&](uint32_t pos, int32_t n, uint32_t key) {
+  int64_t tile_phys = 0;  // stage B: where the current tile's four keys lie in the [piece][cap] arrays
+  auto emit = [&](uint32_t pos, int32_t n, int c) {
     if (pos < static_cast<uint32_t>(kk)) {
-      if constexpr (STAGE == 0) sel_out[pos] = n;
-      if constexpr (STAGE == 1) {
-        sel_out[pos] = static_cast<int32_t>(row_off) + n;
-        cand[pos] = key_to_score(key);
-      }
-      if constexpr (STAGE == 2) sel_out[pos] = remap[n];
+      if constexpr (STAGE == 0) sel_out[pos] = n + c;
+      if constexpr (STAGE == 2) sel_out[pos] = remap[tile_phys + c];  // position in the original row
     }
   };
   for_each_tile([&](int j, const uint32_t(&k4)[4]) {
@@ -568,13 +575,17 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
     uint32_t gt_before = base_gt + (excl & 0xFFFFu);
     uint32_t eq_before = base_eq + (excl >> 16);
     const int32_t nn = static_cast<int32_t>(wbase + static_cast<int64_t>(j) * kWaveTile);
+    if constexpr (STAGE == 2) {
+      int valid;
+      tile_phys = nn < N ? locate(nn, valid) : 0;
+    }
     if ((tot >> 16) == 0) {
       // no key of this wave tile equals T: the tie count is the same for every slot
       uint32_t pos = gt_before + (eq_before < r_eq ? eq_before : r_eq);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         if (k4[c] > T) {
-          emit(pos, nn + c, k4[c]);
+          emit(pos, nn, c);
           ++pos;
         }
       }
@@ -584,7 +595,7 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
         const bool gt = k4[c] > T;
         const bool eq = (k4[c] == T) && T;
         if (gt || (eq && eq_before < r_eq)) {
-          emit(gt_before + (eq_before < r_eq ? eq_before : r_eq), nn + c, k4[c]);
+          emit(gt_before + (eq_before < r_eq ? eq_before : r_eq), nn, c);
         }
         gt_before += gt ? 1u : 0u;
         eq_before += eq ? 1u : 0u;
@@ -596,29 +607,180 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   TB_MARK(6);
 }
 
+template <int NT>
+__global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void select_kernel(SelectArgs a) {
+  select_body<NT, 0>(a, nullptr);
+}
+
+// ---- two-stage selection, stage A.  One workgroup per (row, piece); the piece's keys stay in
+// registers (NT tiles per wave, piece_len <= 65536).  Every piece of a row takes the same
+// sample of the row's candidates (4096 positions spread over [lo, hi)) and so arrives at the
+// same threshold: the lower end of the bracket that the one-workgroup selection would use.
+template <int NT>
+__global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void prefilter_kernel(SelectArgs a) {
+  __shared__ uint32_t s_hist[kHistBins];
+  __shared__ __attribute__((aligned(16))) Found s_found;
+  __shared__ uint32_t s_part[kSelWaves];
+  __shared__ uint32_t s_wcnt[kSelWaves];
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  const int wave = tid / kWave;
+  const int u = blockIdx.x / a.pieces, c = blockIdx.x % a.pieces;
+  const int64_t base = c * a.piece_len;
+  int64_t n_c = a.N - base;
+  n_c = n_c < 0 ? 0 : (n_c > a.piece_len ? a.piece_len : n_c);
+  int64_t lo_c = a.lo - base, hi_c = a.hi - base;  // the candidates of this piece, as positions inside it
+  lo_c = lo_c < 0 ? 0 : (lo_c > n_c ? n_c : lo_c);
+  hi_c = hi_c < lo_c ? lo_c : (hi_c > n_c ? n_c : hi_c);
+  const float* row = a.scores + static_cast<int64_t>(u) * a.score_stride;
+  const float* s = row + base;
+  const int64_t last4 = n_c > 0 ? ((n_c - 1) & ~int64_t{3}) : 0;
+  const int64_t wbase = static_cast<int64_t>(wave) * NT * kWaveTile + lane * 4;
+
+  TB_MARK(20);
+  // the sample of the whole row: 256 clusters of 16 adjacent scores (one 64-byte line each, so
+  // that sampling does not pull the whole row through the caches once more), spread evenly over
+  // the candidates; four threads share a cluster with one 128-bit load each
+  const int64_t span = a.hi - a.lo;
+  int64_t sp = a.lo + ((tid / 4) * span) / (kSelThreads / 4);
+  sp = (sp & ~int64_t{15}) + (tid % 4) * 4;
+  const int64_t row_last4 = (a.N - 1) & ~int64_t{3};
+  uint32_t keys[NT][4];
+  float4 sraw;
+  {
+    float4 raw[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) raw[j] = load_scores4(s, last4, wbase + j * kWaveTile);
+    sraw = load_scores4(row, row_last4, sp);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+      keys_of4(raw[j], static_cast<int>(lo_c), static_cast<int>(hi_c), wbase + j * kWaveTile, keys[j]);
+  }
+
+  for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
+  if (tid < 8) reinterpret_cast<uint32_t*>(&s_found)[tid] = 0;
+  __syncthreads();
+  TB_MARK(21);
+  uint32_t n_valid = 0;
+  {
+    uint32_t sk[4];
+    keys_of4(sraw, a.lo, a.hi, sp, sk);  // (a cluster may straddle an end of the candidate range)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (sk[i]) {
+        atomicAdd(&s_hist[sk[i] >> kTopShift], 1u);
+        ++n_valid;
+      }
+    }
+  }
+  TB_MARK(22);
+  const int kk = a.kk;
+  const Found fb = find_bins(s_hist, n_valid, s_part, &s_found, [&](uint32_t n_s, uint32_t& na, uint32_t& nb) {
+    const float frac = static_cast<float>(kk) / static_cast<float>(span);
+    const float ks_f = frac * static_cast<float>(n_s);
+    const float margin = 6.0f * sqrtf(ks_f * (1.0f - frac)) + 4.0f;
+    const float lo_f = ks_f + margin;
+    na = 0u;
+    nb = lo_f >= static_cast<float>(n_s) ? n_s + 1u : static_cast<uint32_t>(lo_f) + 1u;
+  });
+  uint32_t b_lo = (fb.need_b <= fb.extra_total) ? fb.bin_b : 1u;
+  if (b_lo < 1u) b_lo = 1u;
+  const uint32_t t_lo = b_lo << kTopShift;  // keys from here up are kept
+  TB_MARK(23);
+
+  // ordered compaction of the piece's kept keys (prefix sums as in the selection itself)
+  uint32_t pre[NT];
+  uint32_t run = 0;
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) cnt += keys[j][e] >= t_lo ? 1u : 0u;
+    const uint32_t incl = wave_incl_scan_u32(cnt);
+    pre[j] = run + incl - cnt;
+    run += __builtin_amdgcn_readlane(incl, kWave - 1);
+  }
+  if (lane == 0) s_wcnt[wave] = run;
+  __syncthreads();
+  TB_MARK(24);
+  uint32_t total;
+  const uint32_t wave_base = wave_entries_scan(s_wcnt, total);
+  if (tid == 0) a.piece_count[static_cast<int64_t>(u) * a.pieces + c] = static_cast<int32_t>(total);
+  int32_t* out_idx = a.cand_idx + (static_cast<int64_t>(u) * a.pieces + c) * a.cap;
+  float* out_score = a.cand_score + (static_cast<int64_t>(u) * a.pieces + c) * a.cap;
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    uint32_t pos = wave_base + pre[j];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (keys[j][e] >= t_lo) {
+        if (pos < static_cast<uint32_t>(a.cap)) {
+          out_idx[pos] = static_cast<int32_t>(base + wbase + j * kWaveTile + e);
+          out_score[pos] = key_to_score(keys[j][e]);  // same key again in stage B
+        }
+        ++pos;
+      }
+    }
+  }
+  TB_MARK(25);
+}
+
+// ---- stage B.  One workgroup per row: builds the table of the pieces' kept keys and selects
+// among them, or -- when the pieces kept fewer than kk keys or one of them overflowed -- selects
+// on the original row (one streaming workgroup: slow, but it only happens when the sample of
+// stage A was wildly unrepresentative).
+template <int NT>
+__global__ __launch_bounds__(kSelThreads, 4) void stage_b_kernel(SelectArgs a) {
+  __shared__ uint32_t s_ptab[2 * kMaxPieces + 2];
+  __shared__ uint32_t s_ok;
+  TB_MARK(29);
+  if (threadIdx.x == 0) {
+    const int32_t* cnt = a.piece_count + static_cast<int64_t>(blockIdx.x) * a.pieces;
+    uint32_t at = 0, kept = 0, ok = 1;
+    for (int c = 0; c < kMaxPieces; ++c) {
+      const uint32_t n = c < a.pieces ? static_cast<uint32_t>(cnt[c]) : 0u;
+      if (n > static_cast<uint32_t>(a.cap)) ok = 0;
+      s_ptab[c] = at;
+      s_ptab[kMaxPieces + 1 + c] = n;
+      at += (n + 3u) & ~3u;
+      kept += n;
+    }
+    s_ptab[kMaxPieces] = at;
+    if (at > static_cast<uint32_t>(NT * kTileElts)) ok = 0;  // more than this instance holds in registers
+    s_ok = (ok && kept >= static_cast<uint32_t>(a.kk)) ? 1u : 0u;
+  }
+  __syncthreads();
+  TB_MARK(30);
+  if (s_ok) {
+    select_body<NT, 2>(a, s_ptab);
+  } else {
+    select_body<0, 0>(a, nullptr);
+  }
+}
+
 }  // namespace
 
 namespace {
 
-template <int STAGE>
-tb_status launch_one(const SelectArgs& a, int64_t workgroups, int64_t row_len, hipStream_t st) {
+tb_status launch_whole(const SelectArgs& a, int64_t units, hipStream_t st) {
   SelectArgs b = a;
-  const int32_t tiles = static_cast<int32_t>((row_len + kTileElts - 1) / kTileElts);  // per wave
+  const int32_t tiles = static_cast<int32_t>((a.N + kTileElts - 1) / kTileElts);  // per wave
   b.tiles_per_wave = tiles;
-  dim3 grid(static_cast<unsigned>(workgroups));
+  dim3 grid(static_cast<unsigned>(units));
   dim3 block(kSelThreads);
   if (tiles <= 1)
-    hipLaunchKernelGGL((select_kernel<1, STAGE>), grid, block, 0, st, b);
+    hipLaunchKernelGGL(select_kernel<1>, grid, block, 0, st, b);
   else if (tiles <= 2)
-    hipLaunchKernelGGL((select_kernel<2, STAGE>), grid, block, 0, st, b);
+    hipLaunchKernelGGL(select_kernel<2>, grid, block, 0, st, b);
   else if (tiles <= 4)
-    hipLaunchKernelGGL((select_kernel<4, STAGE>), grid, block, 0, st, b);
+    hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, st, b);
   else if (tiles <= 8)
-    hipLaunchKernelGGL((select_kernel<8, STAGE>), grid, block, 0, st, b);
+    hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, st, b);
   else if (tiles <= 16)
-    hipLaunchKernelGGL((select_kernel<16, STAGE>), grid, block, 0, st, b);
+    hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, st, b);
   else
-    hipLaunchKernelGGL((select_kernel<0, STAGE>), grid, block, 0, st, b);
+    hipLaunchKernelGGL(select_kernel<0>, grid, block, 0, st, b);
   return hip_status(hipGetLastError());
 }
 
@@ -636,48 +798,55 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   a.idx = L.idx;
   a.count = L.count;
   a.idx_cap = L.idx_cap;
-  a.chunks = 1;
-  a.chunk_len = 0;
+  a.tiles_per_wave = 0;
+  a.pieces = 1;
+  a.piece_len = 0;
+  a.cap = 0;
+  a.cand_idx = nullptr;
   a.cand_score = nullptr;
-  a.remap = nullptr;
-  a.emit_lo = L.lo;
-  a.emit_hi = L.hi;
-  a.emit_N = L.N;
-  const SelectPlan plan = select_plan(L.units, L.N, L.kk);
-  if (plan.chunks <= 1 || !L.scratch || L.scratch_bytes < select_scratch_bytes(L.units, plan))
-    return launch_one<0>(a, L.units, L.N, st);
+  a.piece_count = nullptr;
+  const SelectPlan plan = select_plan(L.units, L.hi - L.lo, L.N, L.kk);
+  if (plan.pieces <= 1 || !L.scratch || L.scratch_bytes < select_scratch_bytes(L.units, plan))
+    return launch_whole(a, L.units, st);
 
-  // stage A: every piece keeps its own top-kk; positions and scores land in the scratch arrays
-  int32_t* cand_idx = static_cast<int32_t*>(L.scratch);
-  float* cand_score = reinterpret_cast<float*>(cand_idx + L.units * plan.cand_stride);
-  SelectArgs sa = a;
-  sa.chunks = plan.chunks;
-  sa.chunk_len = plan.chunk_len;
-  sa.idx = cand_idx;
-  sa.idx_cap = plan.cand_stride;
-  sa.cand_score = cand_score;
-  sa.count = nullptr;
-  const tb_status rc = launch_one<1>(sa, L.units * plan.chunks, plan.chunk_len, st);
-  if (rc != TB_OK) return rc;
-  // stage B: the kk largest among what the pieces kept (the same host arithmetic as the kernel's)
-  int64_t n_cand = 0;
-  for (int c = 0; c < plan.chunks; ++c) {
-    const int64_t base = c * plan.chunk_len;
-    int64_t n_c = L.N - base;
-    n_c = n_c < 0 ? 0 : (n_c > plan.chunk_len ? plan.chunk_len : n_c);
-    int64_t lo_c = L.lo - base, hi_c = L.hi - base;
-    lo_c = lo_c < 0 ? 0 : (lo_c > n_c ? n_c : lo_c);
-    hi_c = hi_c < lo_c ? lo_c : (hi_c > n_c ? n_c : hi_c);
-    n_cand += L.kk < hi_c - lo_c ? L.kk : hi_c - lo_c;
+  // scratch: kept positions, kept scores ([units][pieces][cap] each), then the pieces' counts
+  const int64_t per_unit = static_cast<int64_t>(plan.pieces) * plan.cap;
+  a.pieces = plan.pieces;
+  a.piece_len = plan.piece_len;
+  a.cap = plan.cap;
+  a.cand_idx = static_cast<int32_t*>(L.scratch);
+  a.cand_score = reinterpret_cast<float*>(a.cand_idx + L.units * per_unit);
+  a.piece_count = reinterpret_cast<int32_t*>(a.cand_score + L.units * per_unit);
+  a.tiles_per_wave = static_cast<int32_t>((L.N + kTileElts - 1) / kTileElts);  // for the fall-back on the whole row
+  dim3 block(kSelThreads);
+  {
+    dim3 grid(static_cast<unsigned>(L.units * plan.pieces));
+    const int tiles = static_cast<int>((plan.piece_len + kTileElts - 1) / kTileElts);
+    if (tiles <= 1)
+      hipLaunchKernelGGL(prefilter_kernel<1>, grid, block, 0, st, a);
+    else if (tiles <= 2)
+      hipLaunchKernelGGL(prefilter_kernel<2>, grid, block, 0, st, a);
+    else if (tiles <= 4)
+      hipLaunchKernelGGL(prefilter_kernel<4>, grid, block, 0, st, a);
+    else if (tiles <= 8)
+      hipLaunchKernelGGL(prefilter_kernel<8>, grid, block, 0, st, a);
+    else
+      hipLaunchKernelGGL(prefilter_kernel<16>, grid, block, 0, st, a);
+    if (hipGetLastError() != hipSuccess) return TB_ERR_HIP;
   }
-  SelectArgs sb = a;
-  sb.scores = cand_score;
-  sb.score_stride = plan.cand_stride;
-  sb.N = n_cand;
-  sb.lo = 0;
-  sb.hi = static_cast<int32_t>(n_cand);
-  sb.remap = cand_idx;
-  return launch_one<2>(sb, L.units, n_cand, st);
+  {
+    dim3 grid(static_cast<unsigned>(L.units));
+    const int tiles = static_cast<int>((per_unit + kTileElts - 1) / kTileElts);  // at most: the pieces' capacity
+    if (tiles <= 2)
+      hipLaunchKernelGGL(stage_b_kernel<2>, grid, block, 0, st, a);
+    else if (tiles <= 4)
+      hipLaunchKernelGGL(stage_b_kernel<4>, grid, block, 0, st, a);
+    else if (tiles <= 8)
+      hipLaunchKernelGGL(stage_b_kernel<8>, grid, block, 0, st, a);
+    else  // (more than 65536 kept keys falls back to the whole row inside the kernel)
+      hipLaunchKernelGGL(stage_b_kernel<16>, grid, block, 0, st, a);
+  }
+  return hip_status(hipGetLastError());
 }
 
 }  // namespace tb

@@ -179,6 +179,20 @@ def test_select_streamed_rows(oracle, N, ks):
         check_select(oracle, tied, N, ks[-1], 3, 5, ws=ws)
         check_select(oracle, asc, N, ks[0], 0, 0, ws=ws)
         check_select(oracle, -asc, N, ks[0], 2, 0, ws=ws)
+    # rows whose sample misleads the first stage (it looks at 256 clusters of 16 adjacent scores):
+    # huge values exactly there -> the pieces keep fewer keys than the budget; hugely negative ones
+    # exactly there -> the pieces keep far more than they have room for.  Both must
+    # end in the same lists (the second stage then selects on the whole row).
+    span = N
+    cluster = torch.tensor([((c * span) // 256) & ~15 for c in range(256)])
+    pos = (cluster[:, None] + torch.arange(16)[None, :]).reshape(-1)
+    pos = pos[pos < N]
+    huge = scores.clone()
+    huge[:, :, pos.to(DEV)] = 1e30
+    check_select(oracle, huge, N, min(N // 8, 3 * len(pos)), 0, 0)
+    low = scores.clone()
+    low[:, :, pos.to(DEV)] = -1e30
+    check_select(oracle, low, N, ks[0], 0, 0)
 
 
 @pytest.mark.parametrize("N", [777, 9000, 66000])
