@@ -79,10 +79,10 @@ tb_status tb_score(const tb_cache_desc* desc, const void* q_imp, const void* Kim
  *   idx = [0,lo) ++ ascending(kept) ++ [hi,N),   count = lo + kk + (N - hi).
  * idx: int32 [B][Hq][idx_cap], idx_cap >= lo + kk + (N - hi); entries beyond count are left
  * untouched.  count: int32 [B][Hq].  ws / ws_bytes are optional (NULL / 0 is fine): the selection
- * keeps its scratch on chip, except that long rows on few heads (N >= 131072, B*Hq <= 128) are
- * cut into pieces that are selected by several compute units and then combined, which needs
- * tb_workspace_bytes(TB_OP_SELECT, desc, sink + k + window) bytes; with less, one workgroup
- * selects the whole row (same result, slower). */
+ * keeps its scratch on chip, except that long rows (N >= 131072 with a budget of at most an
+ * eighth of the candidates) are cut into pieces that are filtered by several compute units and
+ * then combined, which needs tb_workspace_bytes(TB_OP_SELECT, desc, sink + k + window) bytes;
+ * with less, one workgroup selects the whole row (same result, slower). */
 tb_status tb_select_topk(const tb_cache_desc* desc, const float* scores, int64_t score_stride, int32_t k,
                          int32_t sink, int32_t window, int32_t* idx, int32_t* count, int64_t idx_cap, void* ws,
                          size_t ws_bytes, void* stream);

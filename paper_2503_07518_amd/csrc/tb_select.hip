@@ -20,6 +20,10 @@
 // prefix sums (DPP scans inside a 256-key wave tile, running totals along the wave's span, 16
 // wave totals across the workgroup) -- no atomic slot grabbing, so the result is ordered and
 // reproducible.  No global scratch is used.
+//
+// Long rows take two launches (prefilter_kernel, stage_b_kernel; see there): pieces of the row
+// keep the keys at or above a threshold sampled from the whole row, and the selection above runs
+// on what they kept.
 #include "tb_device.h"
 #include "tb_internal.h"
 
