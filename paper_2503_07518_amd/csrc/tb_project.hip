@@ -1,6 +1,7 @@
 // Key-cache projection K_imp = K W: rows [n_begin, n_end) of every (b, kv-head).
 //
-// Two forms.  project_kernel serves every shape, the one-row append of a decode step included:
+// Three forms.  project_rows_kernel takes up to four rows (the append of a decode step) with one
+// wave per row.  project_kernel serves every shape:
 // a workgroup projects a tile of 64 cache rows, W (D x Dimp) and the K tile are staged in LDS as
 // fp32, 64 columns of the head dimension per round; thread (row, quarter) accumulates Dimp/4
 // adjacent outputs in fp32 and rounds once (round to nearest even) to the storage type.
@@ -176,9 +177,40 @@ __global__ __launch_bounds__(kMfmaThreads) void project_mfma_kernel(ProjectArgs 
 #undef TB_LOAD_TILE
 }
 
+// ---- a few rows (the append of a decode step): one wave per cache row, no LDS, no barrier.
+// Lane l accumulates output column l % DIMP over the slice l / DIMP of the head dimension (W rows
+// are read coalesced, the K element is the same for all lanes of a slice); the slices are then
+// added across lanes.  The whole chain is two dependent loads deep.
+template <typename T, int D, int DIMP>
+__global__ __launch_bounds__(kWave) void project_rows_kernel(ProjectArgs a) {
+  constexpr int SLICES = kWave / DIMP;  // 4, 2 or 1 lanes per output column
+  constexpr int DS = D / SLICES;        // head-dimension elements per slice
+  const int lane = threadIdx.x;
+  const int col = lane % DIMP, slice = lane / DIMP;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int64_t row = a.n_begin + blockIdx.x;
+  const T* w = static_cast<const T*>(a.W) + (a.per_head_w ? static_cast<int64_t>(h) * D * DIMP : 0) +
+               static_cast<int64_t>(slice) * DS * DIMP + col;
+  const T* k = static_cast<const T*>(a.K) + b * a.k_stride_b + h * a.k_stride_h + row * a.k_stride_n + slice * DS;
+  float acc = 0.f;
+#pragma unroll 16
+  for (int d = 0; d < DS; ++d) acc = fmaf(to_float(k[d]), to_float(w[static_cast<int64_t>(d) * DIMP]), acc);
+#pragma unroll
+  for (int off = DIMP; off < kWave; off <<= 1) acc += __shfl_xor(acc, off, kWave);
+  if (slice == 0) {
+    T* o = static_cast<T*>(a.Kimp) + b * a.ki_stride_b + h * a.ki_stride_h + row * a.ki_stride_n + col;
+    store_elt(o, acc);
+  }
+}
+
 template <typename T, int D, int DIMP>
 tb_status launch_tdd(const tb_cache_desc& d, ProjectArgs a, hipStream_t st) {
   const int64_t rows = a.n_end - a.n_begin;
+  if (rows <= 4) {
+    dim3 grid(static_cast<unsigned>(rows), d.Hkv, d.B);
+    hipLaunchKernelGGL((project_rows_kernel<T, D, DIMP>), grid, dim3(kWave), 0, st, a);
+    return hip_status(hipGetLastError());
+  }
   if constexpr (std::is_same<T, bf16_t>::value && DIMP == 32) {
     if (rows >= kMfmaMinRows) {  // batched projection: enough rows to fill the matrix cores
       int tiles = kMfmaMaxTilesPerWave;

@@ -35,6 +35,11 @@ def randn(shape, dtype, seed, scale=1.0):
     (torch.bfloat16, 64, 64, 129, 1),
     (torch.float32, 128, 64, 65, 3),
     (torch.bfloat16, 128, 16, 1, 1),
+    # up to four rows: the one-wave-per-row form of the decode-step append
+    (torch.float32, 64, 64, 3, 3),
+    (torch.bfloat16, 128, 32, 2, 1),
+    (torch.bfloat16, 64, 16, 4, 3),
+    (torch.float32, 128, 32, 5, 1),
     # enough rows for the matrix-core form (bf16, Dimp 32), ragged last tile
     (torch.bfloat16, 128, 32, 4133, 1),
     (torch.bfloat16, 64, 32, 2501, 3),
