@@ -15,6 +15,16 @@
 #include "tb_device.h"
 #include "tb_internal.h"
 
+#ifdef TB_PROBE
+__device__ unsigned long long tb_attn_probe[16];
+#define TB_AMARK(i, cond)                                                   \
+  do {                                                                      \
+    if ((cond) && threadIdx.x == 0) tb_attn_probe[i] = wall_clock64();      \
+  } while (0)
+#else
+#define TB_AMARK(i, cond)
+#endif
+
 namespace tb {
 namespace {
 
@@ -80,6 +90,9 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
   const int b = blockIdx.z;
   const int64_t u = static_cast<int64_t>(b) * a.Hq + h;
   const int hkv = h / a.g;
+  const bool probe_wg = blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0;
+  (void)probe_wg;
+  TB_AMARK(0, probe_wg);
 
   const int64_t wg_beg = static_cast<int64_t>(split) * a.rows_per_wg;
   const int rows_per_wave = a.rows_per_wg / kAttnWaves;
@@ -151,6 +164,7 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     n = n < 0 ? 0 : (n >= a.N ? a.N - 1 : n);
     n_next = (lane < TILE && i < w_end) ? static_cast<int32_t>(n) : -1;
   }
+  TB_AMARK(1, probe_wg && n_next >= -1);
   for (int64_t t0 = w_beg; t0 < w_end; t0 += TILE) {
     const int32_t n_mine = n_next;
     typename Pack16<T>::Raw kraw[kLoadsPerTile], vraw[kLoadsPerTile];  // kept packed until used
@@ -209,6 +223,7 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     }
   }
 
+  TB_AMARK(2, probe_wg);
   // merge the row groups of the wave
 #pragma unroll
   for (int off = LPR; off < kWave; off <<= 1) {
@@ -260,6 +275,7 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
   // Partials are written and read with device-scope atomic accesses (they go to the memory
   // side of the per-XCD L2 caches), so the hand-over needs no cache write-back or invalidate:
   // the stores have completed when the barrier is passed, then the ticket is taken.
+  TB_AMARK(3, probe_wg);
   float* part = a.partials + (u * a.nsplit + split) * (D + 2);
   if (tid < D) __hip_atomic_store(&part[tid], o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (tid == 0) {
@@ -267,12 +283,15 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     __hip_atomic_store(&part[D + 1], L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
+  TB_AMARK(4, probe_wg);
   if (tid == 0) {
     const uint32_t ticket = __hip_atomic_fetch_add(&a.counters[u * kCounterStrideWords], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (ticket == static_cast<uint32_t>(a.nsplit - 1)) ? 1u : 0u;
   }
   __syncthreads();
+  TB_AMARK(5, probe_wg);
   if (!s_last) return;
+  TB_AMARK(6, u == 0);
   // Combine the partials: thread (d, lane-group j) walks splits j, j+G, ... in chunks whose
   // loads are all issued before the first is used (a dependent chain of device-scope loads
   // would cost one memory round trip per split); the G groups are then merged through LDS in
@@ -309,6 +328,7 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
         }
       }
     }
+    TB_AMARK(7, u == 0);
     __syncthreads();  // s_acc / s_m / s_l were last read before the partial was published
     s_acc[j][d] = og;
     if (d == 0) {
@@ -334,6 +354,7 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     }
   }
   if (tid == 0) __hip_atomic_store(&a.counters[u * kCounterStrideWords], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  TB_AMARK(8, u == 0);
 }
 
 template <typename T, int D>
