@@ -7,7 +7,7 @@ cache, top-k selection per query head, decode attention over the gathered K/V ro
 cycles through several distinct copies of the layer's buffers so that no step finds its cache
 in the 256 MB last-level cache.
 
-Prints ONE JSON line (see README / DESIGN for the fields):
+Prints ONE JSON line; its main fields:
   value          microseconds per step (lower is better)
   roofline       achieved HBM GB/s of the dominant kernel (gather attention) against 8 TB/s,
                  timed live with events on the launch stream
