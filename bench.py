@@ -86,7 +86,7 @@ class LayerBuffers:
         return sum(t.numel() * t.element_size() for t in (self.K, self.V, self.Kimp, self.scores, self.idx))
 
 
-def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False):
+def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False, mode=0):
     """The prediction-interval loop of the config (cfg.steps decode steps, a prediction every
     cfg.P steps, neighbours of radius cfg.radius on the steps in between) as one HIP graph:
     mean time per step, and the rows that attention gathers on the two kinds of step.
@@ -102,7 +102,7 @@ def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False):
     qis = [data["q_imp"][t].contiguous() for t in range(cfg.steps)]
 
     dec = interval.IntervalDecoder(K, V, W, Kimp, cfg.Hq, cfg.k, cfg.P, cfg.radius, sink=cfg.sink,
-                                   window=cfg.window, sm_scale=cfg.sm_scale, buffered=buffered)
+                                   window=cfg.window, sm_scale=cfg.sm_scale, buffered=buffered, mode=mode)
 
     def loop():
         dec.N_pred = dec.projected_upto = None  # the cache is back at its post-prefill length
@@ -157,6 +157,7 @@ def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False):
         us_migrate = e0.elapsed_time(e1) * 1e3 / 10
     return {
         "attention_reads": "migrated buffers" if buffered else "cache rows (fused gather)",
+        "neighbours": "union of +-radius" if mode == 0 else "cluster-aware (one free position per selected token)",
         "migration_us": None if us_migrate is None else round(us_migrate, 3),
         "steps": cfg.steps, "P": cfg.P, "radius": cfg.radius, "prediction_steps": n_pred,
         "reuse_steps": cfg.steps - n_pred, "us_per_step_mean": round(us_loop / cfg.steps, 3),
@@ -379,6 +380,7 @@ def main():
     if cfg.P > 1:
         result["interval_loop"] = time_interval_loop(cfg, tb, workloads, torch)
         result["interval_loop_buffered"] = time_interval_loop(cfg, tb, workloads, torch, buffered=True)
+        result["interval_loop_cluster_neighbours"] = time_interval_loop(cfg, tb, workloads, torch, mode=1)
 
     if not args.no_cpu_baseline:
         import numpy as np
