@@ -5,7 +5,7 @@
 // a workgroup projects a tile of 64 cache rows, W (D x Dimp) and the K tile are staged in LDS as
 // fp32, 64 columns of the head dimension per round; thread (row, quarter) accumulates Dimp/4
 // adjacent outputs in fp32 and rounds once (round to nearest even) to the storage type.
-// project_mfma_kernel is the batched form for bf16 with Dimp = 32 (a window of appended rows,
+// project_mfma_kernel is the batched form for bf16 with Dimp = 16 or 32 (a window of appended rows,
 // or the whole cache after prefill) on the matrix cores.
 #include "tb_device.h"
 #include "tb_internal.h"
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjectArgs a) {
   }
 }
 
-// ---- batched form for bf16 with Dimp = 32 on the matrix cores ---------------------------------
+// ---- batched form for bf16 with Dimp = 16 or 32 on the matrix cores ---------------------------------
 // The projection of many rows is a (rows x D) x (D x 32) contraction with 25 flop per byte:
 // above what the plain fp32 FMA path sustains, so it goes through v_mfma_f32_32x32x8_bf16_1k.
 // A wave projects tiles of 32 cache rows: the tile is loaded with coalesced 128-bit loads,
@@ -104,17 +104,19 @@ constexpr int kMfmaMaxTilesPerWave = 4;
 constexpr int kMfmaMinRows = 2048;                           // below this the plain form is used
 constexpr int kMfmaTargetWgs = 2048;                         // shorten the waves' spans to reach this
 
-template <int D>
+// DIMP = 16 runs the same 32-column tile with the upper 16 columns of W zero (twice the matrix
+// work of what is needed, which the memory-bound kernel does not notice) and stores the lower 16.
+template <int D, int DIMP>
 __global__ __launch_bounds__(kMfmaThreads) void project_mfma_kernel(ProjectArgs a) {
-  constexpr int DIMP = 32;
+  static_assert(DIMP == 16 || DIMP == 32, "the MFMA tile has 32 columns");
   constexpr int KSTEPS = D / 8;
   constexpr int PITCH = D * 2 + 16;         // bytes per staged row (padded against bank conflicts)
-  constexpr int OPITCH = DIMP * 2 + 16;     // bytes per row of the rounded output tile
+  constexpr int OPITCH = 32 * 2 + 16;       // bytes per row of the rounded output tile
   constexpr int LPR = D * 2 / 16;           // lanes per row in the coalesced load
   constexpr int RPI = kWave / LPR;          // rows per load instruction
   constexpr int NLD = 32 / RPI;             // load instructions per tile
   __shared__ __attribute__((aligned(16))) unsigned char s_k[kMfmaWaves][32 * PITCH];
-  __shared__ __attribute__((aligned(16))) uint16_t s_wt[DIMP][D + 4];
+  __shared__ __attribute__((aligned(16))) uint16_t s_wt[32][D + 4];
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
@@ -124,6 +126,8 @@ __global__ __launch_bounds__(kMfmaThreads) void project_mfma_kernel(ProjectArgs 
 
   const uint16_t* w = static_cast<const uint16_t*>(a.W) + (a.per_head_w ? static_cast<int64_t>(h) * D * DIMP : 0);
   for (int i = tid; i < D * DIMP; i += kMfmaThreads) s_wt[i % DIMP][i / DIMP] = w[i];
+  if (DIMP < 32)
+    for (int i = tid; i < D * (32 - DIMP); i += kMfmaThreads) s_wt[DIMP + i / D][i % D] = 0;
   __syncthreads();
   mfma_bf16x4 bop[KSTEPS];
 #pragma unroll
@@ -167,9 +171,10 @@ __global__ __launch_bounds__(kMfmaThreads) void project_mfma_kernel(ProjectArgs 
 #pragma unroll
     for (int i = 0; i < 16; ++i)
       *reinterpret_cast<uint16_t*>(tile + (8 * (i / 4) + 4 * kh + (i % 4)) * OPITCH + col * 2) = f32_to_bf16_rne(acc[i]);
+    constexpr int PARTS = DIMP * 2 / 16;  // 128-bit pieces of an output row
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int c = lane + kWave * j, r = c / 4, part = c % 4;
+    for (int j = 0; j < 32 * PARTS / kWave; ++j) {
+      const int c = lane + kWave * j, r = c / PARTS, part = c % PARTS;
       const uint4 o = *reinterpret_cast<const uint4*>(tile + r * OPITCH + part * 16);
       if (row0 + r < a.n_end) *reinterpret_cast<uint4*>(ob + (row0 + r) * a.ki_stride_n + part * 8) = o;
     }
@@ -211,7 +216,7 @@ tb_status launch_tdd(const tb_cache_desc& d, ProjectArgs a, hipStream_t st) {
     hipLaunchKernelGGL((project_rows_kernel<T, D, DIMP>), grid, dim3(kWave), 0, st, a);
     return hip_status(hipGetLastError());
   }
-  if constexpr (std::is_same<T, bf16_t>::value && DIMP == 32) {
+  if constexpr (std::is_same<T, bf16_t>::value && (DIMP == 16 || DIMP == 32)) {
     if (rows >= kMfmaMinRows) {  // batched projection: enough rows to fill the matrix cores
       int tiles = kMfmaMaxTilesPerWave;
       auto wgs = [&](int t) {
@@ -221,7 +226,7 @@ tb_status launch_tdd(const tb_cache_desc& d, ProjectArgs a, hipStream_t st) {
       while (tiles > 1 && wgs(tiles) * d.Hkv * d.B < kMfmaTargetWgs) tiles >>= 1;
       a.tiles_per_wave = tiles;
       dim3 grid(static_cast<unsigned>(wgs(tiles)), d.Hkv, d.B);
-      hipLaunchKernelGGL((project_mfma_kernel<D>), grid, dim3(kMfmaThreads), 0, st, a);
+      hipLaunchKernelGGL((project_mfma_kernel<D, DIMP>), grid, dim3(kMfmaThreads), 0, st, a);
       return hip_status(hipGetLastError());
     }
   }

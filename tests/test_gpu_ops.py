@@ -44,6 +44,8 @@ def randn(shape, dtype, seed, scale=1.0):
     (torch.bfloat16, 128, 32, 4133, 1),
     (torch.bfloat16, 64, 32, 2501, 3),
     (torch.bfloat16, 128, 32, 2048, 3),
+    (torch.bfloat16, 128, 16, 3000, 1),   # the paper's interaction dimension, on the same tile
+    (torch.bfloat16, 64, 16, 2111, 3),
 ])
 def test_project_keys(oracle, dtype, D, Dimp, N, Hw):
     say(f"project dtype={dtype} D={D} Dimp={Dimp} N={N} Hw={Hw}")
