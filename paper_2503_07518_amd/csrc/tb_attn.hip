@@ -1,7 +1,8 @@
 // Decode attention over a per-head list of selected rows (gather fused into the kernel: no
 // intermediate "important buffer" copy is made).
 //
-// Work split: grid (nsplit, Hq, B).  A workgroup of 4 waves takes a contiguous slice of the
+// Work split: nsplit workgroups per (b, h) (placed per XCD when heads share KV rows, see the
+// kernel).  A workgroup of 4 waves takes a contiguous slice of the
 // head's list; each wave walks its part in tiles of 8*GPW rows, where GPW = 64/LPR row groups
 // and LPR = D*sizeof(T)/16 lanes cover one row with a 128-bit load each (bf16, D=128: 16
 // lanes per 256 B row, 4 rows per wave instruction, 32-row tiles).  All K and V loads of a
@@ -29,6 +30,7 @@ namespace tb {
 namespace {
 
 constexpr int kAttnThreads = 256;
+constexpr int kXcds = 8;  // accelerator complex dies of the chip, each with its own L2
 constexpr int kAttnWaves = kAttnThreads / kWave;
 #ifndef TB_ATTN_LOADS_PER_TILE
 #define TB_ATTN_LOADS_PER_TILE 8
@@ -56,7 +58,7 @@ struct AttnArgs {
   float* lse;
   float* partials;
   uint32_t* counters;
-  int32_t Hq, g, rows_per_wg, nsplit;
+  int32_t Hq, g, rows_per_wg, nsplit, n_kv_groups;
   // buffered form: the listed rows have been copied to per-query-head buffers
   // [B][Hq][buf_cap][D] in list order (slot i of the list is buffer row i); idx is unused
   const void* Kbuf;
@@ -85,12 +87,30 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
   const int wave = tid / kWave;
   const int grp = lane / LPR;
   const int sub = lane % LPR;
-  const int split = blockIdx.x;
-  const int h = blockIdx.y;
-  const int b = blockIdx.z;
+  // Workgroups go to the 8 XCDs round-robin by their linear index, and every XCD has an L2 of
+  // its own: with grouped queries, the query heads that share a KV head are given to one XCD, so
+  // that rows picked by several of them are fetched into one L2 once.  KV group (b, hkv) number
+  // k lives on XCD k % 8; slot s of an XCD is (its k-th group, head of the group, split).  (If
+  // the hardware places workgroups differently, the mapping is just another order of the work.)
+  int split, h, b, hkv;
+  if (a.g > 1) {
+    const int per_group = a.g * a.nsplit;
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int kvg = xcd + kXcds * (slot / per_group);
+    if (kvg >= a.n_kv_groups) return;  // the last round of groups does not fill all XCDs
+    const int within = slot % per_group;
+    split = within % a.nsplit;
+    hkv = kvg % (a.Hq / a.g);
+    b = kvg / (a.Hq / a.g);
+    h = hkv * a.g + within / a.nsplit;
+  } else {
+    split = blockIdx.x;
+    h = blockIdx.y;
+    b = blockIdx.z;
+    hkv = h;
+  }
   const int64_t u = static_cast<int64_t>(b) * a.Hq + h;
-  const int hkv = h / a.g;
-  const bool probe_wg = blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0;
+  const bool probe_wg = u == 0 && split == 0;
   (void)probe_wg;
   TB_AMARK(0, probe_wg);
 
@@ -389,7 +409,9 @@ tb_status launch_td(const AttnLaunch& L, hipStream_t st) {
   a.Kbuf = L.Kbuf;
   a.Vbuf = L.Vbuf;
   a.buf_cap = L.buf_cap;
+  a.n_kv_groups = d.B * d.Hkv;
   dim3 grid(L.plan.nsplit, d.Hq, d.B);
+  if (a.g > 1) grid = dim3(static_cast<unsigned>(kXcds * ((a.n_kv_groups + kXcds - 1) / kXcds) * a.g * a.nsplit));
   if (L.Kbuf)
     hipLaunchKernelGGL((attn_kernel<T, D, true>), grid, dim3(kAttnThreads), 0, st, a);
   else
