@@ -58,7 +58,7 @@ struct AttnArgs {
   float* lse;
   float* partials;
   uint32_t* counters;
-  int32_t Hq, g, rows_per_wg, nsplit, n_kv_groups;
+  int32_t Hq, g, rows_per_wg, nsplit, n_kv_groups, xcd_map;
   // buffered form: the listed rows have been copied to per-query-head buffers
   // [B][Hq][buf_cap][D] in list order (slot i of the list is buffer row i); idx is unused
   const void* Kbuf;
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
   // k lives on XCD k % 8; slot s of an XCD is (its k-th group, head of the group, split).  (If
   // the hardware places workgroups differently, the mapping is just another order of the work.)
   int split, h, b, hkv;
-  if (a.g > 1) {
+  if (a.xcd_map) {
     const int per_group = a.g * a.nsplit;
     const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
     const int kvg = xcd + kXcds * (slot / per_group);
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     split = blockIdx.x;
     h = blockIdx.y;
     b = blockIdx.z;
-    hkv = h;
+    hkv = h / a.g;
   }
   const int64_t u = static_cast<int64_t>(b) * a.Hq + h;
   const bool probe_wg = u == 0 && split == 0;
@@ -410,8 +410,10 @@ tb_status launch_td(const AttnLaunch& L, hipStream_t st) {
   a.Vbuf = L.Vbuf;
   a.buf_cap = L.buf_cap;
   a.n_kv_groups = d.B * d.Hkv;
+  // per-XCD placement pays when heads share KV rows and the KV groups spread evenly over the XCDs
+  a.xcd_map = (a.g > 1 && (a.n_kv_groups % kXcds == 0 || a.n_kv_groups >= 8 * kXcds)) ? 1 : 0;
   dim3 grid(L.plan.nsplit, d.Hq, d.B);
-  if (a.g > 1) grid = dim3(static_cast<unsigned>(kXcds * ((a.n_kv_groups + kXcds - 1) / kXcds) * a.g * a.nsplit));
+  if (a.xcd_map) grid = dim3(static_cast<unsigned>(kXcds * ((a.n_kv_groups + kXcds - 1) / kXcds) * a.g * a.nsplit));
   if (L.Kbuf)
     hipLaunchKernelGGL((attn_kernel<T, D, true>), grid, dim3(kAttnThreads), 0, st, a);
   else
