@@ -22,7 +22,8 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
   }
   const int64_t target_wgs = TB_ATTN_TARGET_WGS;
   int64_t want = (target_wgs + units - 1) / units;
-  const int64_t max_split = (max_rows + tile_rows_per_wg - 1) / tile_rows_per_wg;
+  // (a workgroup is worth its hand-over from two tiles per wave on)
+  const int64_t max_split = max_rows / (2 * tile_rows_per_wg);
   if (want > max_split) want = max_split;
   if (want < 1) want = 1;
   int64_t rows = (max_rows + want - 1) / want;
