@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X datasheet HBM3E bandwidth
 
 # HBM bytes per launch of the gather-attention kernel measured with rocprofv3 PMC counters
 # (FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB device copy; profiles/decode_step_C2_hbm_traffic.txt)
-MEASURED_ATTN_TRAFFIC = {"C2_llama3_8b_32k": 54.86e6 + 0.56e6}
+MEASURED_ATTN_TRAFFIC = {"C2_llama3_8b_32k": 46.87e6 + 0.29e6}
 
 
 def parse_args():
