@@ -26,8 +26,12 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
   const int64_t max_split = max_rows / (2 * tile_rows_per_wg);
   if (want > max_split) want = max_split;
   if (want < 1) want = 1;
+  // equal shares, rounded up to whole wave instructions (4 rows x 4 waves for 256-byte rows) rather
+  // than whole tiles: a ragged last tile per wave costs less than a last workgroup round that
+  // only some compute units take part in
+  const int64_t granule = tile_rows_per_wg / kAttnLoadsPerTile;
   int64_t rows = (max_rows + want - 1) / want;
-  rows = (rows + tile_rows_per_wg - 1) / tile_rows_per_wg * tile_rows_per_wg;
+  rows = (rows + granule - 1) / granule * granule;
   p.rows_per_wg = static_cast<int>(rows);
   p.nsplit = static_cast<int>((max_rows + rows - 1) / rows);
   p.max_split = static_cast<int>(want);

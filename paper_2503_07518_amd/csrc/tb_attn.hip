@@ -32,10 +32,7 @@ namespace {
 constexpr int kAttnThreads = 256;
 constexpr int kXcds = 8;  // accelerator complex dies of the chip, each with its own L2
 constexpr int kAttnWaves = kAttnThreads / kWave;
-#ifndef TB_ATTN_LOADS_PER_TILE
-#define TB_ATTN_LOADS_PER_TILE 4
-#endif
-constexpr int kLoadsPerTile = TB_ATTN_LOADS_PER_TILE;
+constexpr int kLoadsPerTile = kAttnLoadsPerTile;
 // occupancy the register allocation is held to: 4 waves per SIMD = 4 workgroups per CU, so that a
 // launch of up to 1024 workgroups is resident at once (no second round of workgroups)
 #ifndef TB_ATTN_WAVES_PER_SIMD

@@ -111,6 +111,10 @@ struct GatherLaunch {
 };
 tb_status launch_gather(const GatherLaunch& a, hipStream_t st);
 int attn_tile_rows_per_wg(int dtype, int D);
+#ifndef TB_ATTN_LOADS_PER_TILE
+#define TB_ATTN_LOADS_PER_TILE 4
+#endif
+constexpr int kAttnLoadsPerTile = TB_ATTN_LOADS_PER_TILE;  // K (and V) gathers of a lane per tile
 tb_status launch_attn(const AttnLaunch& a, hipStream_t st);
 
 // Query predictor of a producer layer (LN + two-layer MLP), see tb_predict.hip.
