@@ -115,6 +115,17 @@ tb_status tb_sparse_decode_attn(const tb_cache_desc* desc, const void* q, const 
                                 int64_t tail_begin, int64_t tail_end, float sm_scale, float* out, float* lse,
                                 void* ws, size_t ws_bytes, void* stream);
 
+/* Head-less form of tb_sparse_decode_attn (Appendix "Additional Efficiency Evaluation": the
+ * predictor gives one importance per token per layer, with no head dimension, so one token list
+ * serves every head of the layer).  idx: [B][idx_cap], count: [B]; every query head h of batch
+ * element b attends over idx[b,0:count[b]] followed by [tail_begin, tail_end).  Such a list is
+ * what tb_score and tb_select_topk produce under a descriptor with Hq = Hkv = 1 (one importance
+ * head).  All other arguments, results and errors as tb_sparse_decode_attn. */
+tb_status tb_sparse_decode_attn_shared(const tb_cache_desc* desc, const void* q, const void* K, const void* V,
+                                       const int32_t* idx, const int32_t* count, int64_t idx_cap,
+                                       int64_t max_count, int64_t tail_begin, int64_t tail_end, float sm_scale,
+                                       float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
+
 /* Migration of selected rows into the "Important Buffer" (Sec. 3.3 "Inference Setup": the
  * paper keeps the attended tokens in contiguous buffers and copies the selection there on
  * prediction steps).  Kbuf/Vbuf[b,h,i,:] = K/V[b,h/g,idx[b,h,i],:] for i < min(count[b,h], max_count).

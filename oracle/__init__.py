@@ -207,6 +207,16 @@ def sparse_decode_attn(q, K, V, idx, count, dtype, sm_scale: float) -> Tuple[np.
     return out, lse
 
 
+def sparse_decode_attn_shared(q, K, V, idx, count, dtype, sm_scale: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Head-less selection (Appendix "Additional Efficiency Evaluation": one importance per token
+    per layer): the single list idx [B,cap], count [B] is what every head of the batch element
+    attends over.  By definition this is sparse_decode_attn with the list repeated for each head."""
+    B, Hq, _ = np.asarray(q).shape
+    idx = _arr(idx, np.int32).reshape(B, 1, -1)
+    count = _arr(count, np.int32).reshape(B, 1)
+    return sparse_decode_attn(q, K, V, np.repeat(idx, Hq, axis=1), np.repeat(count, Hq, axis=1), dtype, sm_scale)
+
+
 def predict_queries(h, gamma, beta, W1, b1, W2, b2, G: int, Hq: int, Dimp: int, dtype, ln_eps: float = 1e-5):
     """Query prediction of a producer layer (Sec. 3.1 "Query prediction"): LayerNorm over the
     model dimension, then a two-layer MLP (exact-erf GELU; the paper does not name the

@@ -23,6 +23,7 @@ TB_OP_SELECT, TB_OP_ATTN, TB_OP_DECODE_STEP = 1, 2, 3
 
 EXPORTS = (
     "tb_project_keys", "tb_score", "tb_select_topk", "tb_expand_neighbors", "tb_sparse_decode_attn",
+    "tb_sparse_decode_attn_shared",
     "tb_gather_kv", "tb_buffered_decode_attn", "tb_predict_queries", "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_status_string", "tb_version",
 )
 
@@ -70,6 +71,7 @@ def load_library() -> ctypes.CDLL:
     L.tb_select_topk.argtypes = [dp, vp, i64, i32, i32, i32, vp, vp, i64, vp, sz, vp]
     L.tb_expand_neighbors.argtypes = [i32, i32, i64, i32, i32, vp, vp, i64, vp, vp, i64, vp]
     L.tb_sparse_decode_attn.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, i64, f32, vp, vp, vp, sz, vp]
+    L.tb_sparse_decode_attn_shared.argtypes = L.tb_sparse_decode_attn.argtypes
     L.tb_decode_step.argtypes = [dp, vp, vp, f32, vp, vp, vp, i32, i32, i32, f32, vp, i64, vp, vp, i64, vp, vp,
                                  vp, sz, vp]
     L.tb_gather_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, vp, vp, i64, vp]
@@ -227,6 +229,17 @@ def tb_sparse_decode_attn(desc, q, K, V, idx, count, max_count: int, sm_scale: f
                                                 sm_scale, _ptr(out), _ptr(lse), _ptr(ws),
                                                 ws.numel() * ws.element_size(), _stream(stream)),
            "tb_sparse_decode_attn")
+
+
+def tb_sparse_decode_attn_shared(desc, q, K, V, idx, count, max_count: int, sm_scale: float, out, lse, ws,
+                                 tail_begin: int = 0, tail_end: int = 0, stream=None) -> None:
+    """idx: int32 [B][idx_cap] (or [B][1][idx_cap]), count: int32 [B]; one list for all heads."""
+    assert q.is_contiguous() and out.is_contiguous()
+    _check(load_library().tb_sparse_decode_attn_shared(ctypes.byref(desc), _ptr(q), _ptr(K), _ptr(V), _ptr(idx),
+                                                       _ptr(count), idx.stride(-2), max_count, tail_begin,
+                                                       tail_end, sm_scale, _ptr(out), _ptr(lse), _ptr(ws),
+                                                       ws.numel() * ws.element_size(), _stream(stream)),
+           "tb_sparse_decode_attn_shared")
 
 
 def tb_decode_step(desc, q_imp, Kimp, score_scale: float, q, K, V, k: int, sink: int, window: int, sm_scale: float,

@@ -221,10 +221,11 @@ tb_status tb_expand_neighbors(int32_t B, int32_t Hq, int64_t N, int32_t radius, 
                        cap_out, static_cast<hipStream_t>(stream));
 }
 
-tb_status tb_sparse_decode_attn(const tb_cache_desc* d, const void* q, const void* K, const void* V,
-                                const int32_t* idx, const int32_t* count, int64_t idx_cap, int64_t max_count,
-                                int64_t tail_begin, int64_t tail_end, float sm_scale, float* out, float* lse,
-                                void* ws, size_t ws_bytes, void* stream) {
+namespace {
+tb_status sparse_attn(const tb_cache_desc* d, const void* q, const void* K, const void* V, const int32_t* idx,
+                      const int32_t* count, int64_t idx_cap, int64_t max_count, int64_t tail_begin,
+                      int64_t tail_end, float sm_scale, float* out, float* lse, void* ws, size_t ws_bytes,
+                      void* stream, bool shared_list) {
   TB_TRY(check_attn_args(d, q, K, V, idx, count, idx_cap, max_count, tail_begin, tail_end, out));
   const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
   if (units == 0) return TB_OK;
@@ -237,7 +238,25 @@ tb_status tb_sparse_decode_attn(const tb_cache_desc* d, const void* q, const voi
                sm_scale, out, lse,
                reinterpret_cast<float*>(static_cast<char*>(ws) + w.part_off),
                reinterpret_cast<uint32_t*>(ws), plan};
+  L.shared_list = shared_list;
   return launch_attn(L, static_cast<hipStream_t>(stream));
+}
+}  // namespace
+
+tb_status tb_sparse_decode_attn(const tb_cache_desc* d, const void* q, const void* K, const void* V,
+                                const int32_t* idx, const int32_t* count, int64_t idx_cap, int64_t max_count,
+                                int64_t tail_begin, int64_t tail_end, float sm_scale, float* out, float* lse,
+                                void* ws, size_t ws_bytes, void* stream) {
+  return sparse_attn(d, q, K, V, idx, count, idx_cap, max_count, tail_begin, tail_end, sm_scale, out, lse, ws,
+                     ws_bytes, stream, false);
+}
+
+tb_status tb_sparse_decode_attn_shared(const tb_cache_desc* d, const void* q, const void* K, const void* V,
+                                       const int32_t* idx, const int32_t* count, int64_t idx_cap,
+                                       int64_t max_count, int64_t tail_begin, int64_t tail_end, float sm_scale,
+                                       float* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  return sparse_attn(d, q, K, V, idx, count, idx_cap, max_count, tail_begin, tail_end, sm_scale, out, lse, ws,
+                     ws_bytes, stream, true);
 }
 
 tb_status tb_gather_kv(const tb_cache_desc* d, const void* K, const void* V, const int32_t* idx, const int32_t* count,

@@ -56,6 +56,7 @@ struct AttnArgs {
   float* partials;
   uint32_t* counters;
   int32_t Hq, g, rows_per_wg, nsplit, n_kv_groups, xcd_map;
+  int32_t shared_list;  // one list and count per batch element, read by all of its heads
   // buffered form: the listed rows have been copied to per-query-head buffers
   // [B][Hq][buf_cap][D] in list order (slot i of the list is buffer row i); idx is unused
   const void* Kbuf;
@@ -123,7 +124,8 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
                                                    hkv * a.v_stride_h) + sub * 16;
   const uint32_t k_row_bytes = static_cast<uint32_t>(a.k_stride_n * sizeof(T));
   const uint32_t v_row_bytes = static_cast<uint32_t>(a.v_stride_n * sizeof(T));
-  const int32_t* list = BUF ? nullptr : a.idx + u * a.idx_cap;
+  const int64_t lu = (!BUF && a.shared_list) ? b : u;  // which list this head reads
+  const int32_t* list = BUF ? nullptr : a.idx + lu * a.idx_cap;
   const char* kbuf = nullptr;
   const char* vbuf = nullptr;
   if (BUF) {
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     const int64_t i = w_beg0 + lane;
     const int64_t i_safe = (i < a.idx_cap) ? i : (a.idx_cap > 0 ? a.idx_cap - 1 : 0);
     const int32_t raw = (lane < TILE && a.idx_cap > 0) ? list[i_safe] : 0;
-    int64_t cnt_now = a.count[u];
+    int64_t cnt_now = a.count[lu];
     cnt_now = cnt_now < 0 ? 0 : (cnt_now > a.max_count ? a.max_count : cnt_now);
     cnt = cnt_now;
     total = cnt + (a.tail_end - a.tail_begin);
@@ -406,6 +408,7 @@ tb_status launch_td(const AttnLaunch& L, hipStream_t st) {
   a.Kbuf = L.Kbuf;
   a.Vbuf = L.Vbuf;
   a.buf_cap = L.buf_cap;
+  a.shared_list = L.shared_list ? 1 : 0;
   a.n_kv_groups = d.B * d.Hkv;
   // per-XCD placement pays when heads share KV rows and the KV groups spread evenly over the XCDs
   a.xcd_map = (a.g > 1 && (a.n_kv_groups % kXcds == 0 || a.n_kv_groups >= 8 * kXcds)) ? 1 : 0;

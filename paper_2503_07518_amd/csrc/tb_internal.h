@@ -95,6 +95,8 @@ struct AttnLaunch {
   const void* Kbuf = nullptr;
   const void* Vbuf = nullptr;
   int64_t buf_cap = 0;
+  // head-less form: idx is [B][idx_cap] and count [B], one list for all heads of a batch element
+  bool shared_list = false;
 };
 
 // Copies the listed rows of K and V into per-query-head buffers [B][Hq][buf_cap][D].

@@ -1,0 +1,96 @@
+"""Head-less selection (Appendix "Additional Efficiency Evaluation": one importance per token per
+layer, no head dimension): scoring and selection run with one importance head, and every
+attention head of the layer reads the one list.  Against the oracle, and against the per-head
+entry point given the same list for every head (which must agree bit for bit)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import DEV, dtype_name, gpu_attn, gpu_score, gpu_select, np_of
+from paper_2503_07518_amd import binding as tb
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def shared_attn(q, K, V, idx, cnt, N, sm_scale, max_count, tail=(0, 0)):
+    B, Hq, D = q.shape
+    d = tb.make_desc(N, Hq, K=K, V=V)
+    ws = tb.new_workspace(tb.TB_OP_ATTN, d, max_count + tail[1] - tail[0])
+    out = torch.full((B, Hq, D), float("nan"), dtype=torch.float32, device=DEV)
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    tb.tb_sparse_decode_attn_shared(d, q, K, V, idx, cnt, max_count, sm_scale, out, lse, ws, tail[0], tail[1])
+    torch.cuda.synchronize()
+    return out, lse
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,D,N,k,sink,window", [
+    (torch.bfloat16, 2, 32, 8, 128, 5000, 1024, 4, 64),   # grouped queries, per-XCD placement
+    (torch.bfloat16, 3, 8, 2, 64, 1301, 200, 1, 17),      # ragged, 3 KV groups per XCD round
+    (torch.float32, 1, 4, 4, 64, 333, 50, 0, 0),          # no grouping
+    (torch.float32, 2, 8, 4, 128, 97, 200, 2, 3),         # budget beyond the candidates: everything
+    (torch.bfloat16, 1, 16, 4, 128, 40000, 4096, 16, 256),  # several workgroups per head
+])
+def test_headless_pipeline(oracle, dtype, B, Hq, Hkv, D, N, k, sink, window):
+    say(f"head-less pipeline dtype={dtype} B={B} Hq={Hq} Hkv={Hkv} D={D} N={N} k={k}")
+    g = torch.Generator().manual_seed(31)
+    Dimp = 16
+    K = torch.randn((B, Hkv, N, D), generator=g).to(dtype).to(DEV)
+    V = torch.randn((B, Hkv, N, D), generator=g).to(dtype).to(DEV)
+    q = torch.randn((B, Hq, D), generator=g).to(dtype).to(DEV)
+    Kimp = torch.randn((B, 1, N, Dimp), generator=g).to(dtype).to(DEV)   # one importance head
+    q_imp = torch.randn((B, 1, Dimp), generator=g).to(dtype).to(DEV)
+    sm = 1.0 / math.sqrt(D)
+
+    scores = gpu_score(q_imp, Kimp, N)
+    idx, cnt = gpu_select(scores, N, k, sink, window)          # [B][1][cap], [B][1]
+    torch.cuda.synchronize()
+    r_scores = oracle.score(np_of(q_imp), np_of(Kimp), dtype_name(Kimp), 1.0)
+    assert np.allclose(np_of(scores)[..., :N], r_scores, rtol=1e-4, atol=1e-5)
+    # the list is checked on the GPU's own scores, so that fp32 rounding decides nothing
+    r_idx, r_cnt = oracle.select_topk(np_of(scores)[..., :N], k, sink, window)
+    assert np.array_equal(np_of(cnt), r_cnt)
+    need = int(r_cnt.max())
+    assert np.array_equal(np_of(idx)[..., :need], r_idx[..., :need])
+
+    out, lse = shared_attn(q, K, V, idx, cnt.reshape(B), N, sm, idx.shape[-1])
+    r_out, r_lse = oracle.sparse_decode_attn_shared(np_of(q), np_of(K), np_of(V), r_idx.reshape(B, -1),
+                                                    r_cnt.reshape(B), dtype_name(K), sm)
+    tol = 2e-2 if dtype == torch.bfloat16 else 1e-5
+    assert np.allclose(np_of(out), r_out, atol=tol, rtol=0)
+    assert np.allclose(np_of(lse), r_lse, atol=1e-3, rtol=1e-4)
+
+    # same rows in the same order through the per-head entry point: identical arithmetic
+    rep_idx = idx.expand(B, Hq, idx.shape[-1]).contiguous()
+    rep_cnt = cnt.expand(B, Hq).contiguous()
+    out2, lse2 = gpu_attn(q, K, V, rep_idx, rep_cnt, N, sm)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(lse, lse2)
+
+
+def test_headless_tail_and_ragged_counts(oracle):
+    """A list reused across a prediction interval: ragged counts per batch element (one empty),
+    a count above max_count (truncated), and the dense tail of appended tokens."""
+    say("head-less attention with tail and ragged counts")
+    g = torch.Generator().manual_seed(32)
+    B, Hq, Hkv, D, N, cap = 3, 8, 4, 128, 900, 300
+    K = torch.randn((B, Hkv, N, D), generator=g).to(torch.bfloat16).to(DEV)
+    V = torch.randn((B, Hkv, N, D), generator=g).to(torch.bfloat16).to(DEV)
+    q = torch.randn((B, Hq, D), generator=g).to(torch.bfloat16).to(DEV)
+    idx = torch.stack([torch.randperm(N - 10, generator=g)[:cap].sort().values for _ in range(B)]).to(torch.int32).to(DEV)
+    cnt = torch.tensor([cap + 50, 0, 123], dtype=torch.int32, device=DEV)
+    max_count, tail = 280, (N - 10, N - 3)
+    out, lse = shared_attn(q, K, V, idx, cnt, N, 0.09, max_count, tail)
+    eff = np.minimum(np_of(cnt), max_count)
+    r_idx = np.full((B, max_count + 7), 0, np.int32)
+    for b in range(B):
+        r_idx[b, :eff[b]] = np_of(idx)[b, :eff[b]]
+        r_idx[b, eff[b]:eff[b] + 7] = np.arange(tail[0], tail[1])
+    r_out, r_lse = oracle.sparse_decode_attn_shared(np_of(q), np_of(K), np_of(V), r_idx, eff + 7, "bf16", 0.09)
+    assert np.allclose(np_of(out), r_out, atol=2e-2, rtol=0)
+    assert np.allclose(np_of(lse), r_lse, atol=1e-3, rtol=1e-4)

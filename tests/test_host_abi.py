@@ -114,6 +114,10 @@ def test_rejects_bad_arguments_without_launching(tb):
     assert L.tb_sparse_decode_attn(r(d), P, P, P, P, P, 100, 100, 990, 1001, 1.0, P, NULL, P, 1 << 24, None) == tb.TB_ERR_INVALID_ARG
     assert L.tb_sparse_decode_attn(r(d), P, P, P, P, P, 100, 100, 0, 0, 1.0, P, NULL, P, 64, None) == tb.TB_ERR_WORKSPACE
     assert L.tb_sparse_decode_attn(r(desc(tb, k_stride_n=100)), P, P, P, P, P, 100, 100, 0, 0, 1.0, P, NULL, P, 1 << 24, None) == tb.TB_ERR_INVALID_ARG
+    # the head-less form takes the same checks
+    assert L.tb_sparse_decode_attn_shared(r(d), P, P, P, P, P, 100, 101, 0, 0, 1.0, P, NULL, P, 1 << 24, None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_sparse_decode_attn_shared(r(d), P, P, P, NULL, P, 100, 100, 0, 0, 1.0, P, NULL, P, 1 << 24, None) == tb.TB_ERR_INVALID_ARG
+    assert L.tb_sparse_decode_attn_shared(r(d), P, P, P, P, P, 100, 100, 0, 0, 1.0, P, NULL, P, 64, None) == tb.TB_ERR_WORKSPACE
     # fused step inherits all of the above
     assert L.tb_decode_step(r(d), P, P, 1.0, P, P, P, 10, 0, 0, 1.0, P, 1000, P, P, 9, P, NULL, P, 1 << 24, None) == tb.TB_ERR_INVALID_ARG
     assert L.tb_decode_step(r(d), P, P, 1.0, P, P, P, 10, 0, 0, 1.0, P, 1000, P, P, 10, P, NULL, P, 64, None) == tb.TB_ERR_WORKSPACE

@@ -450,6 +450,27 @@ def test_attention_gqa_head_mapping(oracle):
 # ------------------------------------------------------------------------------ interval driver
 
 
+def test_attention_shared_list_serves_every_head(oracle):
+    """Head-less selection: all heads of a batch element attend over one list; checked against a
+    library fp64 softmax per head (each head with its own query and its KV group's rows)."""
+    rng = np.random.default_rng(21)
+    B, Hq, Hkv, N, D = 2, 6, 2, 50, 16
+    q = rng.standard_normal((B, Hq, D)).astype(np.float32)
+    K = rng.standard_normal((B, Hkv, N, D)).astype(np.float32)
+    V = rng.standard_normal((B, Hkv, N, D)).astype(np.float32)
+    idx = np.full((B, 20), -1, np.int32)
+    cnt = np.array([13, 20], np.int32)
+    for b in range(B):
+        idx[b, :cnt[b]] = np.sort(rng.choice(N, cnt[b], replace=False))
+    out, lse = oracle.sparse_decode_attn_shared(q, K, V, idx, cnt, "f32", 0.3)
+    for b in range(B):
+        for h in range(Hq):
+            ref, ref_lse = numpy_attention(q[b, h].astype(np.float64), K[b, h // 3].astype(np.float64),
+                                           V[b, h // 3].astype(np.float64), idx[b, :cnt[b]], 0.3)
+            assert np.allclose(out[b, h], ref, rtol=1e-6, atol=1e-7)
+            assert np.allclose(lse[b, h], ref_lse, rtol=1e-6)
+
+
 def test_interval_driver_reduces_to_per_step_path_and_set_sizes(oracle):
     rng = np.random.default_rng(14)
     B, Hq, Hkv, N0, D, d, k, steps = 1, 4, 2, 120, 16, 8, 12, 9
