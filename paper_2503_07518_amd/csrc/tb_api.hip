@@ -8,7 +8,14 @@ namespace tb {
 #define TB_ATTN_TARGET_WGS 512
 #endif
 
-AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
+#ifndef TB_GROUP_TARGET_WGS
+#define TB_GROUP_TARGET_WGS 512
+#endif
+#ifndef TB_GROUP_MIN_TILES
+#define TB_GROUP_MIN_TILES 2
+#endif
+
+AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg, bool grouped) {
   // Aim for two workgroups per compute unit (256 CUs): the gathers of the whole chip are in
   // flight together, and fewer, longer workgroups mean fewer partials to hand over (measured
   // best across the five configurations; 1024 was 1 µs slower on the smallest and 2 µs on the
@@ -20,10 +27,10 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
     p.max_split = 1;
     return p;
   }
-  const int64_t target_wgs = TB_ATTN_TARGET_WGS;
+  const int64_t target_wgs = grouped ? TB_GROUP_TARGET_WGS : TB_ATTN_TARGET_WGS;
   int64_t want = (target_wgs + units - 1) / units;
   // (a workgroup is worth its hand-over from two tiles per wave on)
-  const int64_t max_split = max_rows / (2 * tile_rows_per_wg);
+  const int64_t max_split = max_rows / ((grouped ? TB_GROUP_MIN_TILES : 2) * tile_rows_per_wg);
   if (want > max_split) want = max_split;
   if (want < 1) want = 1;
   // equal shares, rounded up to whole wave instructions (4 rows x 4 waves for 256-byte rows) rather
@@ -36,6 +43,15 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg) {
   p.nsplit = static_cast<int>((max_rows + rows - 1) / rows);
   p.max_split = static_cast<int>(want);
   return p;
+}
+
+// A shared list with grouped queries: one workgroup per (KV group, split) loads every row once
+// for all heads of the group.  That pays when there are enough KV groups to fill the chip with
+// few splits each (the last workgroup of a group combines heads x splits partials with
+// device-scope loads, about 0.1 us per split); with fewer groups the per-head kernel, whose
+// heads share rows through the L2 of their XCD, is faster (8 groups, 3277 rows: 10.9 against 18.7 us).
+bool attn_shared_list_grouped(const tb_cache_desc* d) {
+  return d->Hq > d->Hkv && static_cast<int64_t>(d->B) * d->Hkv >= 32;
 }
 
 SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk) {
@@ -230,7 +246,9 @@ tb_status sparse_attn(const tb_cache_desc* d, const void* q, const void* K, cons
   const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
   if (units == 0) return TB_OK;
   const int64_t rows = max_count + (tail_end - tail_begin);
-  const AttnPlan plan = attn_plan(units, rows, attn_tile_rows_per_wg(d->dtype, d->D));
+  const bool grouped = shared_list && attn_shared_list_grouped(d);
+  const int64_t wg_units = grouped ? static_cast<int64_t>(d->B) * d->Hkv : units;
+  const AttnPlan plan = attn_plan(wg_units, rows, attn_tile_rows_per_wg(d->dtype, d->D), wg_units != units);
   const WsLayout w = ws_layout(units, d->D, plan.nsplit);
   if (!ws || !aligned16(ws) || ws_bytes < w.total) return TB_ERR_WORKSPACE;
   AttnLaunch L{d,   q,   K,   V,
@@ -239,6 +257,7 @@ tb_status sparse_attn(const tb_cache_desc* d, const void* q, const void* K, cons
                reinterpret_cast<float*>(static_cast<char*>(ws) + w.part_off),
                reinterpret_cast<uint32_t*>(ws), plan};
   L.shared_list = shared_list;
+  L.grouped = grouped;
   return launch_attn(L, static_cast<hipStream_t>(stream));
 }
 }  // namespace
@@ -372,7 +391,12 @@ size_t tb_workspace_bytes(int32_t op, const tb_cache_desc* d, int64_t max_count)
     const AttnPlan plan = attn_plan(units, max_count, attn_tile_rows_per_wg(d->dtype, d->D));
     // sized for the largest split count a shorter list could get, so that one workspace serves
     // every call whose list is no longer than max_count
-    const size_t att = ws_layout(units, d->D, plan.max_split).total;
+    size_t att = ws_layout(units, d->D, plan.max_split).total;
+    if (attn_shared_list_grouped(d)) {  // the head-less form splits per KV group, possibly finer
+      const AttnPlan gp = attn_plan(static_cast<int64_t>(d->B) * d->Hkv, max_count, attn_tile_rows_per_wg(d->dtype, d->D), true);
+      const size_t g_att = ws_layout(units, d->D, gp.max_split).total;
+      if (g_att > att) att = g_att;
+    }
     return (op == TB_OP_DECODE_STEP && sel_total > att) ? sel_total : att;
   }
   return 0;

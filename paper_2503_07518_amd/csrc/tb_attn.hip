@@ -317,36 +317,48 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
   // group order.  The order of combination is fixed, so the result is reproducible.
   {
     constexpr int G = kAttnThreads / D;  // split groups: 2 for D=128, 4 for D=64
-    constexpr int CH = 8;                // loads in flight per thread and field
     const int d = tid % D, j = tid / D;
     const float* p0 = a.partials + u * a.nsplit * (D + 2);
     float Mg = -INFINITY, Lg = 0.f, og = 0.f;
-    for (int s0 = j; s0 < a.nsplit; s0 += G * CH) {
-      float mv[CH], lv[CH], ov[CH];
+    // CH loads in flight per thread and field.  A device-scope load is paid per instruction
+    // even when its result is not needed, so the chunk is sized to the split count.
+    auto walk = [&](auto ch_tag) {
+      constexpr int CH = decltype(ch_tag)::value;
+      for (int s0 = j; s0 < a.nsplit; s0 += G * CH) {
+        float mv[CH], lv[CH], ov[CH];
 #pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        const int sp = s0 + c * G;
-        const int sl = sp < a.nsplit ? sp : a.nsplit - 1;
-        mv[c] = __hip_atomic_load(&p0[sl * (D + 2) + D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        lv[c] = __hip_atomic_load(&p0[sl * (D + 2) + D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        ov[c] = __hip_atomic_load(&p0[sl * (D + 2) + d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (sp >= a.nsplit) {
-          mv[c] = -INFINITY;
-          lv[c] = 0.f;
-          ov[c] = 0.f;
+        for (int c = 0; c < CH; ++c) {
+          const int sp = s0 + c * G;
+          const int sl = sp < a.nsplit ? sp : a.nsplit - 1;
+          mv[c] = __hip_atomic_load(&p0[sl * (D + 2) + D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          lv[c] = __hip_atomic_load(&p0[sl * (D + 2) + D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ov[c] = __hip_atomic_load(&p0[sl * (D + 2) + d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (sp >= a.nsplit) {
+            mv[c] = -INFINITY;
+            lv[c] = 0.f;
+            ov[c] = 0.f;
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          const float Mn = fmaxf(Mg, mv[c]);
+          if (Mn > -INFINITY) {
+            const float wa = exp2_safe(Mg - Mn), wb = exp2_safe(mv[c] - Mn);
+            Lg = Lg * wa + lv[c] * wb;
+            og = og * wa + ov[c] * wb;
+            Mg = Mn;
+          }
         }
       }
-#pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        const float Mn = fmaxf(Mg, mv[c]);
-        if (Mn > -INFINITY) {
-          const float wa = exp2_safe(Mg - Mn), wb = exp2_safe(mv[c] - Mn);
-          Lg = Lg * wa + lv[c] * wb;
-          og = og * wa + ov[c] * wb;
-          Mg = Mn;
-        }
-      }
-    }
+    };
+    if (a.nsplit <= G)
+      walk(std::integral_constant<int, 1>{});
+    else if (a.nsplit <= 2 * G)
+      walk(std::integral_constant<int, 2>{});
+    else if (a.nsplit <= 4 * G)
+      walk(std::integral_constant<int, 4>{});
+    else
+      walk(std::integral_constant<int, 8>{});
     TB_AMARK(7, u == 0);
     __syncthreads();  // s_acc / s_m / s_l were last read before the partial was published
     s_acc[j][d] = og;
@@ -374,6 +386,315 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
   }
   if (tid == 0) __hip_atomic_store(&a.counters[u * kCounterStrideWords], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   TB_AMARK(8, u == 0);
+}
+
+// Head-less lists with grouped queries: the GH query heads of a KV head read the same rows, so
+// one workgroup serves all of them: every listed row is loaded once and used GH times (the
+// loads, not the arithmetic, bound this kernel).  Work split and tiling as in attn_kernel, with
+// one workgroup per (b, kv head, split); every lane group keeps GH softmax states and GH
+// accumulator slices.  The partial hand-over uses the counter of the group's first head.
+template <typename T, int D, int GH>
+__global__ __launch_bounds__(kAttnThreads) void attn_group_kernel(AttnArgs a) {
+  constexpr int EPL = Pack16<T>::kElts;
+  constexpr int LPR = D / EPL;
+  constexpr int GPW = kWave / LPR;
+  constexpr int TILE = kLoadsPerTile * GPW;
+  constexpr int OUTS = GH * D;                                     // outputs of the workgroup
+  constexpr int R = (OUTS + kAttnThreads - 1) / kAttnThreads;      // outputs per thread in the merges
+  static_assert(LPR >= 4 && LPR <= 32, "row must span 4..32 lanes");
+
+  __shared__ float s_m[kAttnWaves][GH], s_l[kAttnWaves][GH];
+  __shared__ float s_acc[kAttnWaves][GH][D];
+  __shared__ uint32_t s_last;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  const int wave = tid / kWave;
+  const int grp = lane / LPR;
+  const int sub = lane % LPR;
+  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int64_t u0 = static_cast<int64_t>(b) * a.Hq + static_cast<int64_t>(hkv) * GH;  // first head of the group
+  const bool probe_wg = u0 == 0 && split == 0;
+  (void)probe_wg;
+  TB_AMARK(0, probe_wg);
+
+  const int rows_per_wave = a.rows_per_wg / kAttnWaves;
+  const int64_t w_beg = static_cast<int64_t>(split) * a.rows_per_wg + static_cast<int64_t>(wave) * rows_per_wave;
+
+  const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.K) + b * a.k_stride_b +
+                                                   hkv * a.k_stride_h) + sub * 16;
+  const char* vbase = reinterpret_cast<const char*>(static_cast<const T*>(a.V) + b * a.v_stride_b +
+                                                   hkv * a.v_stride_h) + sub * 16;
+  const uint32_t k_row_bytes = static_cast<uint32_t>(a.k_stride_n * sizeof(T));
+  const uint32_t v_row_bytes = static_cast<uint32_t>(a.v_stride_n * sizeof(T));
+  const int32_t* list = a.idx + b * a.idx_cap;
+
+  float qv[GH][EPL];
+#pragma unroll
+  for (int j = 0; j < GH; ++j) {
+    Pack16<T>::load(static_cast<const T*>(a.q) + (u0 + j) * D + sub * EPL, qv[j]);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qv[j][e] *= a.sm_scale_log2;
+  }
+  float m[GH], l[GH], acc[GH][EPL];
+#pragma unroll
+  for (int j = 0; j < GH; ++j) {
+    m[j] = -INFINITY;
+    l[j] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
+  }
+
+  int64_t cnt = a.count[b];
+  cnt = cnt < 0 ? 0 : (cnt > a.max_count ? a.max_count : cnt);
+  const int64_t total = cnt + (a.tail_end - a.tail_begin);
+  const int64_t w_end = (w_beg + rows_per_wave < total) ? w_beg + rows_per_wave : total;
+  // row numbers of a tile: lanes 0..TILE-1 fetch one entry each (list, then the dense tail)
+  auto fetch_rows = [&](int64_t t0) -> int32_t {
+    const int64_t i = t0 + lane;
+    if (lane < TILE && i < w_end) {
+      int64_t n = (i < cnt) ? static_cast<int64_t>(list[i]) : a.tail_begin + (i - cnt);
+      n = n < 0 ? 0 : (n >= a.N ? a.N - 1 : n);  // keep the gather inside the cache whatever the list holds
+      return static_cast<int32_t>(n);
+    }
+    return -1;
+  };
+  int32_t n_next = fetch_rows(w_beg);
+  TB_AMARK(1, probe_wg && n_next >= -1);
+  for (int64_t t0 = w_beg; t0 < w_end; t0 += TILE) {
+    const int32_t n_mine = n_next;
+    typename Pack16<T>::Raw kraw[kLoadsPerTile], vraw[kLoadsPerTile];
+    bool valid[kLoadsPerTile];
+#pragma unroll
+    for (int t = 0; t < kLoadsPerTile; ++t) {
+      const int32_t n = __shfl(n_mine, t * GPW + grp, kWave);
+      valid[t] = n >= 0;
+      const uint32_t row = valid[t] ? static_cast<uint32_t>(n) : 0u;
+      kraw[t] = Pack16<T>::load_raw(kbase + row * k_row_bytes);
+      vraw[t] = Pack16<T>::load_raw(vbase + row * v_row_bytes);
+    }
+    n_next = fetch_rows(t0 + TILE);
+    __builtin_amdgcn_sched_barrier(0);  // every gather of the tile is in flight before the first is consumed
+    float sc[GH][kLoadsPerTile];
+#pragma unroll
+    for (int t = 0; t < kLoadsPerTile; ++t) {
+      float kf[EPL];
+      Pack16<T>::unpack(kraw[t], kf);
+#pragma unroll
+      for (int j = 0; j < GH; ++j) {
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s = fmaf(qv[j][e], kf[e], s);
+        s = group_allreduce_sum<LPR>(s);
+        sc[j][t] = valid[t] ? s : -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < GH; ++j) {
+      float tmax = sc[j][0];
+#pragma unroll
+      for (int t = 1; t < kLoadsPerTile; ++t) tmax = fmaxf(tmax, sc[j][t]);
+      const float m_new = fmaxf(m[j], tmax);
+      const float m_ref = (m_new > -INFINITY) ? m_new : 0.f;  // nothing seen yet: all weights 0
+      const float alpha = exp2_safe(m[j] - m_ref);
+      l[j] *= alpha;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[j][e] *= alpha;
+#pragma unroll
+      for (int t = 0; t < kLoadsPerTile; ++t) {
+        sc[j][t] = exp2_safe(sc[j][t] - m_ref);  // invalid -> 0
+        l[j] += sc[j][t];
+      }
+      m[j] = m_new;
+    }
+#pragma unroll
+    for (int t = 0; t < kLoadsPerTile; ++t) {
+      float vf[EPL];
+      Pack16<T>::unpack(vraw[t], vf);
+#pragma unroll
+      for (int j = 0; j < GH; ++j)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[j][e] = fmaf(sc[j][t], vf[e], acc[j][e]);
+    }
+  }
+
+  // merge the row groups of the wave, head by head
+  TB_AMARK(2, probe_wg);
+#pragma unroll
+  for (int j = 0; j < GH; ++j) {
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) {
+      const float m_o = __shfl_xor(m[j], off, kWave);
+      const float l_o = __shfl_xor(l[j], off, kWave);
+      const float m_n = fmaxf(m[j], m_o);
+      const float wa = (m_n > -INFINITY) ? exp2_safe(m[j] - m_n) : 0.f;
+      const float wb = (m_n > -INFINITY) ? exp2_safe(m_o - m_n) : 0.f;
+      l[j] = l[j] * wa + l_o * wb;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const float a_o = __shfl_xor(acc[j][e], off, kWave);
+        acc[j][e] = acc[j][e] * wa + a_o * wb;
+      }
+      m[j] = m_n;
+    }
+    if (grp == 0) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s_acc[wave][j][sub * EPL + e] = acc[j][e];
+      if (sub == 0) {
+        s_m[wave][j] = m[j];
+        s_l[wave][j] = l[j];
+      }
+    }
+  }
+  __syncthreads();
+
+  // merge the waves: thread owns outputs (head, element) number tid, tid + 256, ...
+  float M[R], L[R], o[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int e = tid + r * kAttnThreads;
+    const int hh = (e < OUTS) ? e / D : 0, d = e % D;
+    M[r] = -INFINITY;
+    L[r] = 0.f;
+    o[r] = 0.f;
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) M[r] = fmaxf(M[r], s_m[w][hh]);
+    if (M[r] > -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < kAttnWaves; ++w) {
+        const float wgt = exp2_safe(s_m[w][hh] - M[r]);
+        L[r] += s_l[w][hh] * wgt;
+        o[r] += s_acc[w][hh][d] * wgt;
+      }
+    }
+  }
+
+  if (a.nsplit == 1) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int e = tid + r * kAttnThreads;
+      if (e < OUTS) {
+        const int hh = e / D, d = e % D;
+        a.out[(u0 + hh) * D + d] = (L[r] > 0.f) ? o[r] / L[r] : 0.f;
+        if (d == 0 && a.lse) a.lse[u0 + hh] = (L[r] > 0.f) ? M[r] * kLn2 + logf(L[r]) : -INFINITY;
+      }
+    }
+    return;
+  }
+
+  // several workgroups per KV group: publish the partials (device-scope accesses, as in
+  // attn_kernel), take a ticket, the last to arrive combines in split order
+  TB_AMARK(3, probe_wg);
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int e = tid + r * kAttnThreads;
+    if (e < OUTS) {
+      const int hh = e / D, d = e % D;
+      float* part = a.partials + ((u0 + hh) * a.nsplit + split) * (D + 2);
+      __hip_atomic_store(&part[d], o[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (d == 0) {
+        __hip_atomic_store(&part[D], M[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&part[D + 1], L[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+  __syncthreads();
+  TB_AMARK(4, probe_wg);
+  if (tid == 0) {
+    const uint32_t ticket = __hip_atomic_fetch_add(&a.counters[u0 * kCounterStrideWords], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (ticket == static_cast<uint32_t>(a.nsplit - 1)) ? 1u : 0u;
+  }
+  __syncthreads();
+  TB_AMARK(5, probe_wg);
+  if (!s_last) return;
+  TB_AMARK(6, u0 == 0);
+  // Combine: the device-scope loads of a chunk are issued together: per thread its R outputs
+  // of CH splits; the (max, sum) pairs of those splits, the same for all elements of a head,
+  // are fetched once by GH * CH threads and passed through LDS.  Splits are merged in order.
+  // A device-scope load is paid per instruction even when its result is not needed, so the
+  // chunk is sized to the split count.
+  constexpr int kMaxCH = (R <= 2) ? 32 : 16;
+  static_assert(GH * kMaxCH <= kAttnThreads, "one thread per (head, split) pair of a chunk");
+  __shared__ float s_pm[GH][kMaxCH], s_pl[GH][kMaxCH];
+  float Mg[R], Lg[R], og[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    Mg[r] = -INFINITY;
+    Lg[r] = 0.f;
+    og[r] = 0.f;
+  }
+  auto walk = [&](auto ch_tag) {
+    constexpr int CH = decltype(ch_tag)::value < kMaxCH ? decltype(ch_tag)::value : kMaxCH;
+    for (int s0 = 0; s0 < a.nsplit; s0 += CH) {
+      float ov[R][CH];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const int e = tid + r * kAttnThreads;
+        const int hh = (e < OUTS) ? e / D : 0, d = e % D;
+        const float* p0 = a.partials + (u0 + hh) * a.nsplit * (D + 2);
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          const int sl = (s0 + c < a.nsplit) ? s0 + c : a.nsplit - 1;
+          ov[r][c] = __hip_atomic_load(&p0[sl * (D + 2) + d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+      if (tid < GH * CH) {
+        const int hh = tid / CH, c = tid % CH;
+        const float* p0 = a.partials + (u0 + hh) * a.nsplit * (D + 2);
+        const int sl = (s0 + c < a.nsplit) ? s0 + c : a.nsplit - 1;
+        const float pm = __hip_atomic_load(&p0[sl * (D + 2) + D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float pl = __hip_atomic_load(&p0[sl * (D + 2) + D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_pm[hh][c] = (s0 + c < a.nsplit) ? pm : -INFINITY;  // a slot past the last split weighs nothing
+        s_pl[hh][c] = (s0 + c < a.nsplit) ? pl : 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const int e = tid + r * kAttnThreads;
+        const int hh = (e < OUTS) ? e / D : 0;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          const float mv = s_pm[hh][c];
+          const float Mn = fmaxf(Mg[r], mv);
+          if (Mn > -INFINITY) {
+            const float wa = exp2_safe(Mg[r] - Mn), wb = exp2_safe(mv - Mn);
+            Lg[r] = Lg[r] * wa + s_pl[hh][c] * wb;
+            og[r] = og[r] * wa + ov[r][c] * wb;
+            Mg[r] = Mn;
+          }
+        }
+      }
+      __syncthreads();  // the pairs are overwritten by the next chunk
+    }
+  };
+  if (a.nsplit <= 2)
+    walk(std::integral_constant<int, 2>{});
+  else if (a.nsplit <= 4)
+    walk(std::integral_constant<int, 4>{});
+  else if (a.nsplit <= 8)
+    walk(std::integral_constant<int, 8>{});
+  else if (a.nsplit <= 16)
+    walk(std::integral_constant<int, 16>{});
+  else
+    walk(std::integral_constant<int, 32>{});
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int e = tid + r * kAttnThreads;
+    if (e < OUTS) {
+      const int hh = e / D, d = e % D;
+      a.out[(u0 + hh) * D + d] = (Lg[r] > 0.f) ? og[r] / Lg[r] : 0.f;
+      if (d == 0 && a.lse) a.lse[u0 + hh] = (Lg[r] > 0.f) ? Mg[r] * kLn2 + logf(Lg[r]) : -INFINITY;
+    }
+  }
+  TB_AMARK(8, u0 == 0);
+  if (tid == 0) __hip_atomic_store(&a.counters[u0 * kCounterStrideWords], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <typename T, int D, int GH>
+tb_status launch_group(const AttnArgs& a, const AttnLaunch& L, hipStream_t st) {
+  const tb_cache_desc& d = *L.desc;
+  hipLaunchKernelGGL((attn_group_kernel<T, D, GH>), dim3(L.plan.nsplit, d.Hkv, d.B), dim3(kAttnThreads), 0, st, a);
+  return hip_status(hipGetLastError());
 }
 
 template <typename T, int D>
@@ -412,6 +733,12 @@ tb_status launch_td(const AttnLaunch& L, hipStream_t st) {
   a.n_kv_groups = d.B * d.Hkv;
   // per-XCD placement pays when heads share KV rows and the KV groups spread evenly over the XCDs
   a.xcd_map = (a.g > 1 && (a.n_kv_groups % kXcds == 0 || a.n_kv_groups >= 8 * kXcds)) ? 1 : 0;
+  if (L.grouped) {  // the plan was made for one workgroup per KV group
+    if (a.g == 2) return launch_group<T, D, 2>(a, L, st);
+    if (a.g == 4) return launch_group<T, D, 4>(a, L, st);
+    if (a.g == 8) return launch_group<T, D, 8>(a, L, st);
+    return TB_ERR_UNSUPPORTED;
+  }
   dim3 grid(L.plan.nsplit, d.Hq, d.B);
   if (a.xcd_map) grid = dim3(static_cast<unsigned>(kXcds * ((a.n_kv_groups + kXcds - 1) / kXcds) * a.g * a.nsplit));
   if (L.Kbuf)

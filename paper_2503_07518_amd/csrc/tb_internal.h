@@ -33,7 +33,8 @@ struct AttnPlan {
   int max_split;    // upper bound of nsplit for any list no longer than the one planned for
 };
 
-AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg);
+AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg, bool grouped = false);
+bool attn_shared_list_grouped(const tb_cache_desc* d);
 WsLayout ws_layout(int64_t units, int D, int nsplit);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -97,6 +98,7 @@ struct AttnLaunch {
   int64_t buf_cap = 0;
   // head-less form: idx is [B][idx_cap] and count [B], one list for all heads of a batch element
   bool shared_list = false;
+  bool grouped = false;  // shared list served by one workgroup per KV group (plan made for that)
 };
 
 // Copies the listed rows of K and V into per-query-head buffers [B][Hq][buf_cap][D].
