@@ -107,3 +107,36 @@ def test_headless_tail_and_ragged_counts(oracle, B):
     r_out, r_lse = oracle.sparse_decode_attn_shared(np_of(q), np_of(K), np_of(V), r_idx, eff + 7, "bf16", 0.09)
     assert np.allclose(np_of(out), r_out, atol=2e-2, rtol=0)
     assert np.allclose(np_of(lse), r_lse, atol=1e-3, rtol=1e-4)
+
+
+@pytest.mark.parametrize("name", ["C2_llama3_8b_32k", "C3_batched_depth", "C5_long_context"])
+def test_headless_full_size_configs(oracle, name):
+    """The benchmark shapes with one importance head (the first KV head's projected keys):
+    selection bit-exact on the GPU's scores for every batch element, attention on sampled heads
+    (the oracle is given one batch element, one query head and its KV head at a time)."""
+    from paper_2503_07518_amd import workloads
+    cfg = workloads.CONFIGS[name]
+    say(f"head-less full size {name}")
+    data = workloads.make_layer(cfg, layer=3, device=DEV)
+    K, V, W = data["K"], data["V"], data["W"]
+    q, q_imp = data["q"][0].contiguous(), data["q_imp"][0][:, :1].contiguous()
+    B, Hq, Hkv, N, D, g = cfg.B, cfg.Hq, cfg.Hkv, cfg.N, cfg.D, cfg.g
+    Kimp = torch.zeros((B, Hkv, N, cfg.Dimp), dtype=K.dtype, device=DEV)
+    tb.tb_project_keys(tb.make_desc(N, Hq, K=K, V=V, Kimp=Kimp), K, W, Kimp, 0, N)
+    workloads.apply_kimp_row_scale(Kimp, data["kimp_row_scale"])
+    Kimp1 = Kimp[:, :1]                                    # [B][1][N][d'], strided view
+    scores = gpu_score(q_imp, Kimp1, N)
+    idx, cnt = gpu_select(scores, N, cfg.k)
+    torch.cuda.synchronize()
+    r_idx, r_cnt = oracle.select_topk(np_of(scores)[..., :N], cfg.k, 0, 0)
+    assert np.array_equal(np_of(cnt), r_cnt) and np.array_equal(np_of(idx), r_idx)
+    out, lse = shared_attn(q, K, V, idx, cnt.reshape(B), N, cfg.sm_scale, idx.shape[-1])
+    rng = np.random.default_rng(5)
+    for _ in range(4):
+        b, h = int(rng.integers(B)), int(rng.integers(Hq))
+        hk = h // g
+        ro, rl = oracle.sparse_decode_attn_shared(np_of(q[b:b + 1, h:h + 1]), np_of(K[b:b + 1, hk:hk + 1]),
+                                                  np_of(V[b:b + 1, hk:hk + 1]), r_idx[b], r_cnt[b], cfg.dtype,
+                                                  cfg.sm_scale)
+        assert float(np.abs(np_of(out[b, h]) - ro[0, 0]).max()) <= 2e-2
+        assert abs(float(lse[b, h]) - float(rl[0, 0])) <= 1e-4 * max(1.0, abs(float(rl[0, 0])))
