@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X datasheet HBM3E bandwidth
 
 # HBM bytes per launch of the gather-attention kernel measured with rocprofv3 PMC counters
 # (FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB device copy; profiles/decode_step_C2_hbm_traffic.txt)
-MEASURED_ATTN_TRAFFIC = {"C2_llama3_8b_32k": 46.87e6 + 0.29e6}
+MEASURED_ATTN_TRAFFIC = {"C2_llama3_8b_32k": 46.97e6 + 0.35e6}
 
 
 def parse_args():
@@ -46,6 +46,8 @@ def parse_args():
                     help="offloaded cache: K and V in pinned host memory, projected keys on the GPU; "
                          "only the selected rows cross the host link")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-headless", action="store_true",
+                    help="skip the timings of the head-less variant (keeps a profile of the per-head kernels clean)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
 
@@ -316,33 +318,35 @@ def main():
     us_predict = timer(stage_predict)
     bytes_predict = (pw["W1"].numel() + pw["W2"].numel()) * cfg.elt_bytes
 
-    # head-less variant: one importance head per layer (here the first KV head's projected keys),
-    # one token list per batch element that every attention head reads
-    for b in bufs:
-        b.hl_Kimp = b.Kimp[:, :1]
-        b.hl_qimp = b.q_imp[:, :1].contiguous()
-        b.hl_desc = tb.make_desc(cfg.N, 1, Kimp=b.hl_Kimp)
-        b.hl_scores = torch.empty((cfg.B, 1, (cfg.N + 3) // 4 * 4), dtype=torch.float32, device="cuda")
-        b.hl_idx = torch.zeros((cfg.B, 1, b.need), dtype=torch.int32, device="cuda")
-        b.hl_cnt = torch.zeros((cfg.B,), dtype=torch.int32, device="cuda")
-        b.hl_ws = tb.new_workspace(tb.TB_OP_SELECT, b.hl_desc, b.need)
+    us_hl_step = us_hl_attn = None
+    if not args.no_headless:
+        # head-less variant: one importance head per layer (here the first KV head's projected keys),
+        # one token list per batch element that every attention head reads
+        for b in bufs:
+            b.hl_Kimp = b.Kimp[:, :1]
+            b.hl_qimp = b.q_imp[:, :1].contiguous()
+            b.hl_desc = tb.make_desc(cfg.N, 1, Kimp=b.hl_Kimp)
+            b.hl_scores = torch.empty((cfg.B, 1, (cfg.N + 3) // 4 * 4), dtype=torch.float32, device="cuda")
+            b.hl_idx = torch.zeros((cfg.B, 1, b.need), dtype=torch.int32, device="cuda")
+            b.hl_cnt = torch.zeros((cfg.B,), dtype=torch.int32, device="cuda")
+            b.hl_ws = tb.new_workspace(tb.TB_OP_SELECT, b.hl_desc, b.need)
 
-    def headless_attn(b):
-        tb.tb_sparse_decode_attn_shared(b.desc, b.q, b.K, b.V, b.hl_idx, b.hl_cnt, b.need, cfg.sm_scale, b.out,
-                                        b.lse, b.ws)
+        def headless_attn(b):
+            tb.tb_sparse_decode_attn_shared(b.desc, b.q, b.K, b.V, b.hl_idx, b.hl_cnt, b.need, cfg.sm_scale, b.out,
+                                            b.lse, b.ws)
 
-    def headless_step(b):
-        tb.tb_score(b.hl_desc, b.hl_qimp, b.hl_Kimp, 1.0, b.hl_scores)
-        tb.tb_select_topk(b.hl_desc, b.hl_scores, cfg.k, cfg.sink, cfg.window, b.hl_idx, b.hl_cnt, b.hl_ws)
-        headless_attn(b)
+        def headless_step(b):
+            tb.tb_score(b.hl_desc, b.hl_qimp, b.hl_Kimp, 1.0, b.hl_scores)
+            tb.tb_select_topk(b.hl_desc, b.hl_scores, cfg.k, cfg.sink, cfg.window, b.hl_idx, b.hl_cnt, b.hl_ws)
+            headless_attn(b)
 
-    for b in bufs:
-        headless_step(b)
-    torch.cuda.synchronize()
-    us_hl_step = timer(headless_step)
-    us_hl_attn = timer(headless_attn)
-    step(bufs[0])       # restore copy 0's per-head outputs, which the parity check reads
-    torch.cuda.synchronize()
+        for b in bufs:
+            headless_step(b)
+        torch.cuda.synchronize()
+        us_hl_step = timer(headless_step)
+        us_hl_attn = timer(headless_attn)
+        step(bufs[0])       # restore copy 0's per-head outputs, which the parity check reads
+        torch.cuda.synchronize()
 
     elt = cfg.elt_bytes
     bytes_kimp = cfg.B * cfg.Hkv * cfg.N * cfg.Dimp * elt
@@ -398,7 +402,7 @@ def main():
         },
         # head-less selection (one list per batch element for all heads): scoring and selection
         # of one importance head, attention over the shared list
-        "headless": {"us_step": round(us_hl_step, 3), "attn_us": round(us_hl_attn, 3)},
+        "headless": None if us_hl_step is None else {"us_step": round(us_hl_step, 3), "attn_us": round(us_hl_attn, 3)},
         "device_copy_256MiB_GBps": round(copy_gbps, 1),
         "timed_wall_s": round(wall_s, 3),
     }
