@@ -438,6 +438,187 @@ tb_status launch_tb(const PredictArgs& a, hipStream_t st) {
   return hip_status(hipGetLastError());
 }
 
+// ---- batched form on the matrix cores (bf16, 8 sequences or more).  With a batch the two
+// layers are [B x E] x [E x hidden] and [B x hidden] x [hidden x out] products; the FMA kernels
+// above spend one instruction per (weight, sequence) pair, the MFMA form one
+// v_mfma_f32_16x16x16_bf16 per 16 x 16 outputs and 16 inputs.  The batch is the M side (16 rows
+// per tile, rows past B are computed on a clamped row and dropped), 16 output rows of the weight
+// matrix the N side.  A lane loads 8 consecutive inputs of its weight row (one 128-bit load) and
+// of its sequence's activations (fp32, two 128-bit loads); the two halves feed two MFMAs whose
+// 16 inputs are {8q .. 8q+3} and {8q+4 .. 8q+7} of each quarter q of a 32-input step -- any
+// assignment of inputs to the k slots is right as long as both operands use the same one.
+// The fp32 activations enter as a sum of two bf16 numbers (the upper 16 bits, and the remainder
+// rounded to nearest): two MFMAs per weight fragment, 2^-17 relative error per product instead
+// of 2^-9, so the fp32-accumulation contract of the FMA path is kept.
+typedef short mfma_bf16x4 __attribute__((ext_vector_type(4)));
+typedef float mfma_f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t pred_u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMfmaK = 32;            // inputs per step of a wave
+constexpr int kHidMfmaWaves = 16;     // waves of a hidden-layer workgroup: they split the inputs
+constexpr int kOutMfmaWaves = 4;      // waves of an output-layer workgroup: one 16-row tile each
+
+// Operands of one 32-input step for M tile rows `x` (fp32 activations of this lane's sequence,
+// 8 consecutive inputs) and weight row `w` (8 consecutive bf16): acc += x . w over the step.
+__device__ inline void mfma_step(const float (&x)[8], const pred_u32x4& w, mfma_f32x4& acc) {
+  uint32_t hi[8], lo[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    hi[i] = __float_as_uint(x[i]) & 0xFFFF0000u;
+    const uint32_t rem = __float_as_uint(x[i] - __uint_as_float(hi[i]));  // (exact subtraction)
+    lo[i] = (rem + 0x7FFFu + ((rem >> 16) & 1u)) & 0xFFFF0000u;           // to nearest even: no bias
+  }
+  auto pack4 = [](const uint32_t* v) {
+    const uint32_t p0 = (v[0] >> 16) | v[1], p1 = (v[2] >> 16) | v[3];  // element 0 in the low half
+    mfma_bf16x4 r;
+    __builtin_memcpy(&r, &p0, 4);
+    __builtin_memcpy(reinterpret_cast<char*>(&r) + 4, &p1, 4);
+    return r;
+  };
+  mfma_bf16x4 w0, w1;
+  __builtin_memcpy(&w0, &w, 8);
+  __builtin_memcpy(&w1, reinterpret_cast<const char*>(&w) + 8, 8);
+  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pack4(hi), w0, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pack4(lo), w0, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pack4(hi + 4), w1, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pack4(lo + 4), w1, acc, 0, 0, 0);
+}
+
+// The steps k_first, k_first + stride, ... < K of a wave.  The loads of 8/MT steps (weights and
+// activations) are issued before the first of them is used: one memory round trip per chunk
+// instead of one per step.  A step past the end reads a clamped address and is skipped.
+template <int MT>
+__device__ inline void mfma_walk(const bf16_t* wrow, const float* const (&xrow)[MT], int k_first, int stride, int K,
+                                 mfma_f32x4 (&acc)[MT]) {
+  constexpr int CH = 8 / MT;
+  for (int kc = k_first; kc < K; kc += CH * stride) {
+    pred_u32x4 w[CH];
+    float4 xa[CH][MT], xb[CH][MT];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int k = kc + c * stride;
+      const int ks = k < K ? k : K - kMfmaK;
+      w[c] = *reinterpret_cast<const pred_u32x4*>(wrow + ks);
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        xa[c][m] = *reinterpret_cast<const float4*>(xrow[m] + ks);
+        xb[c][m] = *reinterpret_cast<const float4*>(xrow[m] + ks + 4);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      if (kc + c * stride < K) {  // (the same for every lane of the wave)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+          const float x[8] = {xa[c][m].x, xa[c][m].y, xa[c][m].z, xa[c][m].w,
+                              xb[c][m].x, xb[c][m].y, xb[c][m].z, xb[c][m].w};
+          mfma_step(x, w[c], acc[m]);
+        }
+      }
+    }
+  }
+}
+
+// z[b][n] = gelu(W1[n] . xln[b] + b1[n]) for 16 hidden units n and MT*16 sequences per
+// workgroup; the 16 waves take every 16th step of the E inputs and their partial tiles are
+// summed through LDS (in wave order: reproducible).
+template <int MT>
+__global__ __launch_bounds__(kHidMfmaWaves * kWave) void hidden_mfma_kernel(PredictArgs a) {
+  __shared__ float s_red[kHidMfmaWaves][MT][256];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int r = lane % 16, q = lane / 16;
+  const int n0 = blockIdx.x * 16, b0 = blockIdx.y * (16 * MT);
+  const bf16_t* wrow = static_cast<const bf16_t*>(a.W1) + static_cast<int64_t>(n0 + r) * a.E + q * 8;
+  const float* xrow[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    const int b = b0 + m * 16 + r;
+    xrow[m] = a.xln + static_cast<int64_t>(b < a.B ? b : a.B - 1) * a.E + q * 8;
+  }
+  mfma_f32x4 acc[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) acc[m] = mfma_f32x4{0.f, 0.f, 0.f, 0.f};
+  mfma_walk<MT>(wrow, xrow, wave * kMfmaK, kHidMfmaWaves * kMfmaK, a.E, acc);
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) s_red[wave][m][lane * 4 + v] = acc[m][v];
+  __syncthreads();
+  // element e = lane*4 + v of a tile is (sequence 4*(lane/16) + v, unit lane%16)
+  for (int t = tid; t < MT * 256; t += kHidMfmaWaves * kWave) {
+    const int m = t / 256, e = t % 256;
+    float sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < kHidMfmaWaves; ++w) sum += s_red[w][m][e];
+    const int l = e / 4, v = e % 4;
+    const int b = b0 + m * 16 + 4 * (l / 16) + v, n = n0 + l % 16;
+    if (b < a.B) a.z[static_cast<int64_t>(b) * a.hidden + n] = gelu_erf(sum + to_float(static_cast<const bf16_t*>(a.b1)[n]));
+  }
+}
+
+// y[b][o] = W2[o] . z[b] + b2[o] for 16 output rows o per wave and MT*16 sequences, rounded to
+// bf16 and scattered to q_imp[slot][b][head][j].
+template <int MT>
+__global__ __launch_bounds__(kOutMfmaWaves * kWave) void output_mfma_kernel(PredictArgs a) {
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int r = lane % 16, q = lane / 16;
+  const int n_out = a.G * a.Hq * a.Dimp;
+  const int n0 = (blockIdx.x * kOutMfmaWaves + wave) * 16, b0 = blockIdx.y * (16 * MT);
+  if (n0 >= n_out) return;
+  const bf16_t* wrow = static_cast<const bf16_t*>(a.W2) + static_cast<int64_t>(n0 + r) * a.hidden + q * 8;
+  const float* xrow[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    const int b = b0 + m * 16 + r;
+    xrow[m] = a.z + static_cast<int64_t>(b < a.B ? b : a.B - 1) * a.hidden + q * 8;
+  }
+  mfma_f32x4 acc[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) acc[m] = mfma_f32x4{0.f, 0.f, 0.f, 0.f};
+  mfma_walk<MT>(wrow, xrow, 0, kMfmaK, a.hidden, acc);
+  const int o = n0 + r;  // this lane's output row: (slot, head, j), slot outermost
+  const int per_slot = a.Hq * a.Dimp;
+  const int slot = o / per_slot, rest = o % per_slot;
+  const float bias = to_float(static_cast<const bf16_t*>(a.b2)[o]);
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int b = b0 + m * 16 + 4 * q + v;
+      if (b < a.B)
+        store_elt(static_cast<bf16_t*>(a.q_imp) + (static_cast<int64_t>(slot) * a.B + b) * per_slot + rest,
+                  acc[m][v] + bias);
+    }
+}
+
+// bf16 batches of 8 or more whose sizes fit the tiles
+bool mfma_form_serves(const PredictArgs& a) {
+  return a.B >= 8 && a.E % kMfmaK == 0 && a.hidden % kMfmaK == 0 && a.hidden % 16 == 0 &&
+         (a.G * a.Hq * a.Dimp) % 16 == 0 && a.xln != nullptr && (reinterpret_cast<uintptr_t>(a.z) & 15u) == 0;
+}
+
+tb_status launch_mfma(const PredictArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((ln_kernel<bf16_t>), dim3(a.B), dim3(kPredThreads), 0, st, a);
+  if (hipGetLastError() != hipSuccess) return TB_ERR_HIP;
+  const int n_out = a.G * a.Hq * a.Dimp;
+  const bool two = a.B > 16;  // 32 sequences per workgroup read every weight once for two M tiles
+  const unsigned groups = static_cast<unsigned>((a.B + (two ? 32 : 16) - 1) / (two ? 32 : 16));
+  const dim3 hgrid(static_cast<unsigned>(a.hidden / 16), groups), hblock(kHidMfmaWaves * kWave);
+  const dim3 ogrid(static_cast<unsigned>((n_out / 16 + kOutMfmaWaves - 1) / kOutMfmaWaves), groups),
+      oblock(kOutMfmaWaves * kWave);
+  if (two) {
+    hipLaunchKernelGGL((hidden_mfma_kernel<2>), hgrid, hblock, 0, st, a);
+    if (hipGetLastError() != hipSuccess) return TB_ERR_HIP;
+    hipLaunchKernelGGL((output_mfma_kernel<2>), ogrid, oblock, 0, st, a);
+  } else {
+    hipLaunchKernelGGL((hidden_mfma_kernel<1>), hgrid, hblock, 0, st, a);
+    if (hipGetLastError() != hipSuccess) return TB_ERR_HIP;
+    hipLaunchKernelGGL((output_mfma_kernel<1>), ogrid, oblock, 0, st, a);
+  }
+  return hip_status(hipGetLastError());
+}
+
 template <typename T>
 tb_status launch_t(const PredictArgs& a, hipStream_t st) {
   // as many batch rows per workgroup as the batch has and the LDS holds (fp32 rows of E)
@@ -474,6 +655,7 @@ tb_status launch_predict(const PredictLaunch& L, hipStream_t st) {
   a.Hq = L.Hq;
   a.Dimp = L.Dimp;
   a.eps = L.eps;
+  if (L.dtype == TB_BF16 && mfma_form_serves(a)) return launch_mfma(a, st);
   return L.dtype == TB_F32 ? launch_t<float>(a, st) : launch_t<bf16_t>(a, st);
 }
 

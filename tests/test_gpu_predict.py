@@ -23,6 +23,14 @@ def make(B, E, hidden, G, Hq, Dimp, dtype, seed):
     (torch.float32, 3, 1024, 256, 2, 8, 16),
     (torch.float32, 1, 8192, 2048, 1, 4, 8),     # largest supported sizes
     (torch.bfloat16, 2, 64, 8, 3, 2, 8),         # rows shorter than one pass of a wave
+    # batches of 8 or more in bf16: the matrix-core form
+    (torch.bfloat16, 16, 4096, 512, 4, 32, 32),  # one full tile of sequences
+    (torch.bfloat16, 8, 4096, 512, 4, 32, 32),   # half a tile
+    (torch.bfloat16, 20, 1024, 256, 2, 8, 16),   # two tiles per workgroup, the second ragged
+    (torch.bfloat16, 45, 512, 64, 1, 4, 16),     # two workgroup groups along the batch
+    (torch.bfloat16, 9, 96, 32, 3, 2, 8),        # smallest sizes the tiles divide
+    (torch.bfloat16, 16, 4096, 520, 4, 32, 32),  # hidden size not a multiple of 32: the FMA form
+    (torch.float32, 16, 1024, 256, 2, 8, 16),    # fp32 batches stay on the FMA form
 ])
 def test_predict_queries(oracle, dtype, B, E, hidden, G, Hq, Dimp):
     print(f"[case] predictor dtype={dtype} B={B} E={E} hidden={hidden} G={G} Hq={Hq} Dimp={Dimp}", flush=True)
