@@ -447,8 +447,8 @@ tb_status launch_tb(const PredictArgs& a, hipStream_t st) {
 // of its sequence's activations (fp32, two 128-bit loads); the two halves feed two MFMAs whose
 // 16 inputs are {8q .. 8q+3} and {8q+4 .. 8q+7} of each quarter q of a 32-input step -- any
 // assignment of inputs to the k slots is right as long as both operands use the same one.
-// The fp32 activations enter as a sum of two bf16 numbers (the upper 16 bits, and the remainder
-// rounded to nearest): two MFMAs per weight fragment, 2^-17 relative error per product instead
+// The fp32 activations enter as a sum of two bf16 numbers (the value rounded to bf16, and the
+// rounded remainder): two MFMAs per weight fragment, 2^-17 relative error per product instead
 // of 2^-9, so the fp32-accumulation contract of the FMA path is kept.
 typedef short mfma_bf16x4 __attribute__((ext_vector_type(4)));
 typedef float mfma_f32x4 __attribute__((ext_vector_type(4)));
@@ -460,16 +460,23 @@ constexpr int kOutMfmaWaves = 4;      // waves of an output-layer workgroup: one
 
 // Operands of one 32-input step for M tile rows `x` (fp32 activations of this lane's sequence,
 // 8 consecutive inputs) and weight row `w` (8 consecutive bf16): acc += x . w over the step.
+typedef __bf16 pred_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float pred_f32x2 __attribute__((ext_vector_type(2)));
+
 __device__ inline void mfma_step(const float (&x)[8], const pred_u32x4& w, mfma_f32x4& acc) {
-  uint32_t hi[8], lo[8];
+  // pairs of activations -> packed bf16 pairs (round to nearest even; one conversion instruction
+  // per pair on this chip), the remainders x - hi (exact in fp32) the same way
+  uint32_t hi[4], lo[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    hi[i] = __float_as_uint(x[i]) & 0xFFFF0000u;
-    const uint32_t rem = __float_as_uint(x[i] - __uint_as_float(hi[i]));  // (exact subtraction)
-    lo[i] = (rem + 0x7FFFu + ((rem >> 16) & 1u)) & 0xFFFF0000u;           // to nearest even: no bias
+  for (int i = 0; i < 4; ++i) {
+    const pred_bf16x2 h = __builtin_convertvector(pred_f32x2{x[2 * i], x[2 * i + 1]}, pred_bf16x2);
+    __builtin_memcpy(&hi[i], &h, 4);
+    const float r0 = x[2 * i] - __uint_as_float(hi[i] << 16);
+    const float r1 = x[2 * i + 1] - __uint_as_float(hi[i] & 0xFFFF0000u);
+    const pred_bf16x2 l = __builtin_convertvector(pred_f32x2{r0, r1}, pred_bf16x2);
+    __builtin_memcpy(&lo[i], &l, 4);
   }
-  auto pack4 = [](const uint32_t* v) {
-    const uint32_t p0 = (v[0] >> 16) | v[1], p1 = (v[2] >> 16) | v[3];  // element 0 in the low half
+  auto frag = [](uint32_t p0, uint32_t p1) {
     mfma_bf16x4 r;
     __builtin_memcpy(&r, &p0, 4);
     __builtin_memcpy(reinterpret_cast<char*>(&r) + 4, &p1, 4);
@@ -478,10 +485,10 @@ __device__ inline void mfma_step(const float (&x)[8], const pred_u32x4& w, mfma_
   mfma_bf16x4 w0, w1;
   __builtin_memcpy(&w0, &w, 8);
   __builtin_memcpy(&w1, reinterpret_cast<const char*>(&w) + 8, 8);
-  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pack4(hi), w0, acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pack4(lo), w0, acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pack4(hi + 4), w1, acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pack4(lo + 4), w1, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(frag(hi[0], hi[1]), w0, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(frag(lo[0], lo[1]), w0, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(frag(hi[2], hi[3]), w1, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(frag(lo[2], lo[3]), w1, acc, 0, 0, 0);
 }
 
 // The steps k_first, k_first + stride, ... < K of a wave.  The loads of 8/MT steps (weights and
