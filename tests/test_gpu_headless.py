@@ -140,3 +140,23 @@ def test_headless_full_size_configs(oracle, name):
                                                   cfg.sm_scale)
         assert float(np.abs(np_of(out[b, h]) - ro[0, 0]).max()) <= 2e-2
         assert abs(float(lse[b, h]) - float(rl[0, 0])) <= 1e-4 * max(1.0, abs(float(rl[0, 0])))
+
+
+@pytest.mark.parametrize("B", [1, 8])  # per-head kernel / one workgroup per KV group
+def test_headless_degenerate_lists(oracle, B):
+    """No list at all (only the dense tail is attended), and nothing to attend (out = 0,
+    lse = -inf), through both kernels that serve a shared list."""
+    say(f"head-less degenerate lists B={B}")
+    g = torch.Generator().manual_seed(33)
+    Hq, Hkv, D, N = 8, 4, 64, 300
+    K = torch.randn((B, Hkv, N, D), generator=g).to(torch.bfloat16).to(DEV)
+    V = torch.randn((B, Hkv, N, D), generator=g).to(torch.bfloat16).to(DEV)
+    q = torch.randn((B, Hq, D), generator=g).to(torch.bfloat16).to(DEV)
+    idx = torch.zeros((B, 4), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((B,), dtype=torch.int32, device=DEV)
+    out, lse = shared_attn(q, K, V, idx, cnt, N, 0.2, 0, tail=(N - 5, N))
+    r_idx = np.tile(np.arange(N - 5, N, dtype=np.int32), (B, 1))
+    r_out, r_lse = oracle.sparse_decode_attn_shared(np_of(q), np_of(K), np_of(V), r_idx, np.full(B, 5, np.int32), "bf16", 0.2)
+    assert np.allclose(np_of(out), r_out, atol=2e-2, rtol=0) and np.allclose(np_of(lse), r_lse, atol=1e-3, rtol=1e-4)
+    out, lse = shared_attn(q, K, V, idx, cnt, N, 0.2, 4)
+    assert torch.all(out == 0) and torch.all(torch.isinf(lse) & (lse < 0))
