@@ -297,10 +297,14 @@ class IntervalDriver:
     """
 
     def __init__(self, dtype, k: int, P: int, radius: int, sink: int = 0, window: int = 0,
-                 sm_scale: float = 1.0, scale: float = 1.0, expand_on_predict: bool = False, mode: int = 0):
+                 sm_scale: float = 1.0, scale: float = 1.0, expand_on_predict: bool = False, mode: int = 0,
+                 headless: bool = False):
         self.dtype, self.k, self.P, self.radius = dtype, k, P, radius
         self.sink, self.window, self.sm_scale, self.scale = sink, window, sm_scale, scale
         self.expand_on_predict, self.mode = expand_on_predict, mode
+        # head-less variant (Appendix "Additional Efficiency Evaluation"): q_imp [B,1,d'], Kimp
+        # [B,1,N,d']; one list per batch element, attended by every head
+        self.headless = headless
         self.N_pred = None
         self.exp_idx = None
         self.exp_cnt = None
@@ -328,5 +332,8 @@ class IntervalDriver:
                     c = int(self.exp_cnt[b, h])
                     use_idx[b, h, :c] = self.exp_idx[b, h, :c]
                     use_idx[b, h, c:c + extra] = tail
-        out, lse = sparse_decode_attn(q, Kt, Vt, use_idx, use_cnt, self.dtype, self.sm_scale)
+        if self.headless:
+            out, lse = sparse_decode_attn_shared(q, Kt, Vt, use_idx[:, 0], use_cnt[:, 0], self.dtype, self.sm_scale)
+        else:
+            out, lse = sparse_decode_attn(q, Kt, Vt, use_idx, use_cnt, self.dtype, self.sm_scale)
         return out, lse, use_idx, use_cnt

@@ -10,6 +10,10 @@ local window is refreshed every step), and nothing else is touched.
 With ``buffered=True`` the widened selection is migrated into per-query-head buffers on the
 prediction step (the paper's Important Buffer, Sec. 3.3) and the other steps attend over the
 buffers plus the dense tail; the fused form gathers the rows from the cache on every step.
+
+With ``headless=True`` the importance has no head dimension (Appendix "Additional Efficiency
+Evaluation"): ``Kimp`` is ``[B][1][Ncap][d']``, ``q_imp`` is ``[B][1][d']``, one list per batch
+element is selected, widened and attended by every head.
 """
 from __future__ import annotations
 
@@ -21,26 +25,31 @@ from . import binding as tb
 class IntervalDecoder:
     def __init__(self, K, V, W, Kimp, Hq: int, k: int, P: int, radius: int, sink: int = 0, window: int = 0,
                  sm_scale: float = 1.0, score_scale: float = 1.0, mode: int = 0, expand_on_predict: bool = False,
-                 buffered: bool = False):
+                 buffered: bool = False, headless: bool = False):
         self.K, self.V, self.W, self.Kimp = K, V, W, Kimp
         self.B, self.Hkv, self.Ncap, self.D = K.shape
         self.Hq, self.k, self.P, self.radius = Hq, k, P, radius
         self.sink, self.window, self.sm_scale, self.score_scale = sink, window, sm_scale, score_scale
         self.mode, self.expand_on_predict = mode, expand_on_predict
+        self.headless = headless
+        assert not (headless and buffered), "the buffers are per query head"
         dev = K.device
         B = self.B
+        Hl = 1 if headless else Hq  # heads that carry a list of their own
         self.sel_cap = sink + k + window
         mult = (2 * radius + 1) if mode == 0 else 2
         self.exp_cap = min(self.Ncap, mult * self.sel_cap)
-        self.scores = torch.empty((B, Hq, (self.Ncap + 3) // 4 * 4), dtype=torch.float32, device=dev)
-        self.idx = torch.zeros((B, Hq, self.sel_cap), dtype=torch.int32, device=dev)
-        self.cnt = torch.zeros((B, Hq), dtype=torch.int32, device=dev)
-        self.exp_idx = torch.zeros((B, Hq, self.exp_cap), dtype=torch.int32, device=dev)
-        self.exp_cnt = torch.zeros((B, Hq), dtype=torch.int32, device=dev)
+        self.scores = torch.empty((B, Hl, (self.Ncap + 3) // 4 * 4), dtype=torch.float32, device=dev)
+        self.idx = torch.zeros((B, Hl, self.sel_cap), dtype=torch.int32, device=dev)
+        self.cnt = torch.zeros((B, Hl), dtype=torch.int32, device=dev)
+        self.exp_idx = torch.zeros((B, Hl, self.exp_cap), dtype=torch.int32, device=dev)
+        self.exp_cnt = torch.zeros((B, Hl), dtype=torch.int32, device=dev)
         self.out = torch.empty((B, Hq, self.D), dtype=torch.float32, device=dev)
         self.lse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
-        desc = tb.make_desc(self.Ncap, Hq, K=K, V=V, Kimp=Kimp)
+        desc = tb.make_desc(self.Ncap, Hq, K=K, V=V, Kimp=None if headless else Kimp, Dimp=Kimp.shape[3])
         self.ws = tb.new_workspace(tb.TB_OP_DECODE_STEP, desc, self.exp_cap + P)
+        if headless:
+            self.sel_ws = tb.new_workspace(tb.TB_OP_SELECT, tb.make_desc(self.Ncap, 1, Kimp=Kimp), self.sel_cap)
         self.N_pred = None
         self.projected_upto = None
         self.buffered = buffered
@@ -48,8 +57,33 @@ class IntervalDecoder:
             self.Kbuf = torch.empty((B, Hq, self.exp_cap, self.D), dtype=K.dtype, device=dev)
             self.Vbuf = torch.empty_like(self.Kbuf)
 
+    def _step_headless(self, t: int, N_t: int, q: torch.Tensor, q_imp: torch.Tensor):
+        desc = tb.make_desc(N_t, self.Hq, K=self.K, V=self.V, Dimp=self.Kimp.shape[3])
+        attend = tb.tb_sparse_decode_attn_shared
+        if t % self.P == 0:
+            # the importance head (the caller keeps its keys up to date: how they are derived from
+            # the layer's state is not given for this variant, so no projection happens here)
+            d1 = tb.make_desc(N_t, 1, Kimp=self.Kimp)
+            tb.tb_score(d1, q_imp, self.Kimp, self.score_scale, self.scores)
+            tb.tb_select_topk(d1, self.scores, self.k, self.sink, self.window, self.idx, self.cnt, self.sel_ws)
+            tb.tb_expand_neighbors(self.B, 1, N_t, self.radius, self.mode, self.idx, self.cnt, self.exp_idx,
+                                   self.exp_cnt)
+            self.N_pred = N_t
+            if self.expand_on_predict:
+                attend(desc, q, self.K, self.V, self.exp_idx, self.exp_cnt, self.exp_cap, self.sm_scale, self.out,
+                       self.lse, self.ws)
+            else:
+                attend(desc, q, self.K, self.V, self.idx, self.cnt, self.sel_cap, self.sm_scale, self.out, self.lse,
+                       self.ws)
+        else:
+            attend(desc, q, self.K, self.V, self.exp_idx, self.exp_cnt, self.exp_cap, self.sm_scale, self.out,
+                   self.lse, self.ws, tail_begin=self.N_pred, tail_end=N_t)
+        return self.out, self.lse
+
     def step(self, t: int, N_t: int, q: torch.Tensor, q_imp: torch.Tensor):
         """Returns (out, lse) views valid until the next call."""
+        if self.headless:
+            return self._step_headless(t, N_t, q, q_imp)
         desc = tb.make_desc(N_t, self.Hq, K=self.K, V=self.V, Kimp=self.Kimp)
         if t % self.P == 0:
             if self.projected_upto is None:

@@ -160,3 +160,47 @@ def test_headless_degenerate_lists(oracle, B):
     assert np.allclose(np_of(out), r_out, atol=2e-2, rtol=0) and np.allclose(np_of(lse), r_lse, atol=1e-3, rtol=1e-4)
     out, lse = shared_attn(q, K, V, idx, cnt, N, 0.2, 4)
     assert torch.all(out == 0) and torch.all(torch.isinf(lse) & (lse < 0))
+
+
+@pytest.mark.parametrize("B,mode", [(2, 0), (8, 1)])  # 8 x 4 KV heads: the grouped kernel; cluster-aware neighbours
+def test_headless_interval_loop(oracle, B, mode):
+    """Prediction interval with neighbour fetching on one list per batch element: every step
+    against the oracle's driver (selection on the GPU's scores, expansion on the GPU's
+    selection, attention over the widened list plus the rows appended since)."""
+    from paper_2503_07518_amd import interval, workloads
+    say(f"head-less interval loop B={B} mode={mode}")
+    cfg = workloads.C4.scaled(name="C4_headless_small", B=B, Hq=8, Hkv=4, N=3000, k=200, steps=10, P=4,
+                              heavy_per_kv_head=8)
+    data = workloads.make_layer(cfg, device=DEV)
+    K, V, W = data["K"], data["V"], data["W"]
+    Hq, N0, steps = cfg.Hq, cfg.N, 10
+    Ncap = K.shape[2]
+    Kimp_all = torch.zeros((B, cfg.Hkv, Ncap, cfg.Dimp), dtype=K.dtype, device=DEV)
+    tb.tb_project_keys(tb.make_desc(Ncap, Hq, K=K, V=V, Kimp=Kimp_all), K, W, Kimp_all, 0, Ncap)
+    Kimp = Kimp_all[:, :1].contiguous()  # the importance head; rows of future tokens are there but not visible
+    dec = interval.IntervalDecoder(K, V, W, Kimp, Hq, cfg.k, cfg.P, cfg.radius, sm_scale=cfg.sm_scale, mode=mode,
+                                   headless=True)
+    drv = oracle.IntervalDriver(cfg.dtype, cfg.k, cfg.P, cfg.radius, sm_scale=cfg.sm_scale, mode=mode, headless=True)
+    Kn, Vn, Kin = np_of(K), np_of(V), np_of(Kimp)
+    for t in range(steps):
+        N_t = N0 + t
+        q, q_imp = data["q"][t].contiguous(), data["q_imp"][t][:, :1].contiguous()
+        out, lse = dec.step(t, N_t, q, q_imp)
+        torch.cuda.synchronize()
+        if t % cfg.P == 0:
+            drv.step(t, N_t, np_of(q), np_of(q_imp), Kn, Vn, Kin)  # sets N_pred
+            s_idx, s_cnt = oracle.select_topk(np_of(dec.scores)[:, :, :N_t], cfg.k, 0, 0)
+            g_idx, g_cnt = np_of(dec.idx), np_of(dec.cnt)
+            assert np.array_equal(s_cnt, g_cnt) and np.array_equal(s_idx, g_idx[..., : s_idx.shape[-1]])
+            e_idx, e_cnt = oracle.expand_neighbors(g_idx, g_cnt, N_t, cfg.radius, cap_out=dec.exp_idx.shape[-1], mode=mode)
+            assert np.array_equal(np_of(dec.exp_cnt), e_cnt)
+            mask = np.arange(e_idx.shape[-1])[None, None] < e_cnt[..., None]
+            assert np.array_equal(np.where(mask, np_of(dec.exp_idx), -1), np.where(mask, e_idx, -1))
+            drv.exp_idx, drv.exp_cnt = e_idx, e_cnt  # continue the oracle from the GPU's selection
+            ro, rl = oracle.sparse_decode_attn_shared(np_of(q), Kn[:, :, :N_t], Vn[:, :, :N_t], g_idx[:, 0], g_cnt[:, 0],
+                                                      cfg.dtype, cfg.sm_scale)
+        else:
+            ro, rl, _, ucnt = drv.step(t, N_t, np_of(q), np_of(q_imp), Kn, Vn, Kin)
+            assert np.array_equal(ucnt, drv.exp_cnt + (N_t - drv.N_pred))
+        assert float(np.abs(np_of(out) - ro).max()) <= 2e-2, f"step {t}"
+        assert np.abs(np_of(lse) - rl).max() <= 1e-3
