@@ -61,6 +61,9 @@ SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk)
   if (units <= 0 || kk <= 0 || N < 131072 || kk * 8 > candidates) return p;
   int64_t len = 32768;
   if (units * ((N + len - 1) / len) > 512) len = 65536;   // at most two rounds of workgroups on 256 compute units
+  // few rows (a head-less selection has one per batch element): as many pieces as the table of
+  // the second stage holds, so that more compute units take part
+  if (units * ((N + len - 1) / len) < 64) len = (((N + 15) / 16 + 4095) / 4096 * 4096 > 8192) ? ((N + 15) / 16 + 4095) / 4096 * 4096 : 8192;
   if ((N + len - 1) / len > 16) len = ((N + 15) / 16 + 4095) / 4096 * 4096;
   if (len > 65536) return p;                              // a piece has to fit the registers of its workgroup
   const int64_t pieces = (N + len - 1) / len;
