@@ -471,6 +471,30 @@ def test_attention_shared_list_serves_every_head(oracle):
             assert np.allclose(lse[b, h], ref_lse, rtol=1e-6)
 
 
+def test_interval_driver_headless_equals_per_head_path_with_one_importance_head_repeated(oracle):
+    """Head-less loop: one importance head, one list for all heads.  With that importance head
+    (its keys and its query) handed to every head of the per-head loop, every head selects the
+    same list, so both loops must attend over the same rows: equal outputs, step by step,
+    through prediction and reuse steps with neighbours."""
+    rng = np.random.default_rng(15)
+    B, Hq, Hkv, N0, D, d, k, steps = 2, 4, 2, 90, 16, 8, 10, 7
+    Ncap = N0 + steps
+    K = rng.standard_normal((B, Hkv, Ncap, D)).astype(np.float32)
+    V = rng.standard_normal((B, Hkv, Ncap, D)).astype(np.float32)
+    Kimp1 = rng.standard_normal((B, 1, Ncap, d)).astype(np.float32)
+    qs = rng.standard_normal((steps, B, Hq, D)).astype(np.float32)
+    qi1 = rng.standard_normal((steps, B, 1, d)).astype(np.float32)
+    hl = oracle.IntervalDriver("f32", k, P=3, radius=1, sink=1, window=2, sm_scale=0.25, headless=True)
+    ph = oracle.IntervalDriver("f32", k, P=3, radius=1, sink=1, window=2, sm_scale=0.25)
+    for t in range(steps):
+        N_t = N0 + t
+        o1, l1, i1, c1 = hl.step(t, N_t, qs[t], qi1[t], K, V, Kimp1)
+        o2, l2, i2, c2 = ph.step(t, N_t, qs[t], np.repeat(qi1[t], Hq, axis=1), K, V, np.repeat(Kimp1, Hkv, axis=1))
+        assert i1.shape[1] == 1 and np.array_equal(np.repeat(c1, Hq, axis=1), c2)
+        assert all(np.array_equal(i1[:, 0, : c1[:, 0].max()], i2[:, h, : c1[:, 0].max()]) for h in range(Hq))
+        assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
 def test_interval_driver_reduces_to_per_step_path_and_set_sizes(oracle):
     rng = np.random.default_rng(14)
     B, Hq, Hkv, N0, D, d, k, steps = 1, 4, 2, 120, 16, 8, 12, 9
