@@ -251,27 +251,37 @@ def main():
 
     def time_graph(fn, n_steps, warmup):
         """Replay a HIP graph that holds one call per buffer copy (what a serving loop that
-        captures a whole forward pass does); n_steps is rounded up to whole replays."""
-        g = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(g, stream=side):
-                for b in bufs:
-                    fn(b)
-        torch.cuda.current_stream().wait_stream(side)
-        reps = -(-n_steps // copies)
-        for _ in range(max(1, warmup // copies)):
-            g.replay()
+        captures a whole forward pass does).  Exactly n_steps calls are timed: whole replays of
+        that graph plus one replay of a shorter graph for the remainder."""
+        def capture(n_calls):
+            g = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g, stream=side):
+                    for b in bufs[:n_calls]:
+                        fn(b)
+            torch.cuda.current_stream().wait_stream(side)
+            return g
+
+        reps, rest = divmod(n_steps, copies)
+        g_full = capture(copies) if reps or warmup >= copies else None
+        g_rest = capture(rest) if rest else None
+        for _ in range(warmup // copies):
+            g_full.replay()
+        if warmup % copies:
+            capture(warmup % copies).replay()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         cur = torch.cuda.current_stream()
         e0.record(cur)
         for _ in range(reps):
-            g.replay()
+            g_full.replay()
+        if g_rest is not None:
+            g_rest.replay()
         e1.record(cur)
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / (reps * copies), reps * copies
+        return e0.elapsed_time(e1) * 1e3 / n_steps, n_steps
 
     use_graph = not args.no_graph
     steps_done = args.steps
