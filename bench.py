@@ -229,6 +229,21 @@ def main():
     torch.cuda.synchronize()
     copy_gbps = 5 * 2 * (256 << 20) / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
     del cal_src, cal_dst
+    # a plain 128-bit read stream over 1 GiB: the read ceiling of this machine for bandwidth-bound
+    # kernels, quoted next to the data-sheet figure
+    rd_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    rd_sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    rd_src.zero_()
+    for _ in range(2):
+        tb.tb_read_stream_probe(rd_src, rd_sink)
+    torch.cuda.synchronize()
+    ce0.record()
+    for _ in range(5):
+        tb.tb_read_stream_probe(rd_src, rd_sink)
+    ce1.record()
+    torch.cuda.synchronize()
+    read_gbps = 5 * (1 << 30) / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
+    del rd_src, rd_sink
 
     for b in bufs:  # first touch, also fills idx/cnt for the per-stage timings
         step(b)
@@ -295,6 +310,29 @@ def main():
     if not use_graph:
         us_step = time_eager(step, args.steps, args.warmup)
     wall_s = time.perf_counter() - t_wall0
+
+    # spread of the step time: every replay of the full graph timed on its own
+    pct = None
+    if use_graph:
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for b in bufs:
+                    step(b)
+        torch.cuda.current_stream().wait_stream(side)
+        n_rep = max(20, min(200, args.steps // copies))
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_rep + 1)]
+        g.replay()
+        evs[0].record()
+        for i in range(n_rep):
+            g.replay()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        per = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 / copies for i in range(n_rep))
+        pct = {"p10": round(per[n_rep // 10], 3), "median": round(per[n_rep // 2], 3), "p90": round(per[(n_rep * 9) // 10], 3),
+               "replays": n_rep, "steps_per_replay": copies}
 
     timer = (lambda fn: time_graph(fn, args.steps, args.warmup)[0]) if use_graph else (
         lambda fn: time_eager(fn, args.steps, args.warmup))
@@ -413,7 +451,11 @@ def main():
         # head-less selection (one list per batch element for all heads): scoring and selection
         # of one importance head, attention over the shared list
         "headless": None if us_hl_step is None else {"us_step": round(us_hl_step, 3), "attn_us": round(us_hl_attn, 3)},
+        "step_us_spread": pct,
         "device_copy_256MiB_GBps": round(copy_gbps, 1),
+        # measured read ceiling of this machine, and the same kernels' rates against it
+        "read_stream_1GiB_GBps": round(read_gbps, 1),
+        "frac_of_read_stream": {"step": round(step_gbps / read_gbps, 4), "attn_kernel": round(attn_gbps / read_gbps, 4)},
         "timed_wall_s": round(wall_s, 3),
     }
 
@@ -450,9 +492,17 @@ def main():
         gout, _ = oracle.sparse_decode_attn(host["q"], host["K"], host["V"], to_np(b.idx), to_np(b.cnt), cfg.dtype,
                                             cfg.sm_scale)
         attn_err = float(np.abs(gout - to_np(b.out)).max())
+        n_threads = oracle.num_threads()
+        oracle.set_num_threads(1)  # the same step on one core, once
+        t0 = time.perf_counter()
+        oracle.decode_step(host["q"], host["q_imp"], host["K"], host["V"], host["Kimp"], cfg.dtype, cfg.k, cfg.sink,
+                           cfg.window, cfg.sm_scale)
+        t_single = time.perf_counter() - t0
+        oracle.set_num_threads(n_threads)
         result["cpu_baseline"] = {
-            "value": round(t_total / reps * 1e6, 1), "unit": "us/step", "cores": oracle.num_threads(),
+            "value": round(t_total / reps * 1e6, 1), "unit": "us/step", "cores": n_threads,
             "kind": "oracle", "sample": f"{reps} full {cfg.name} steps (score+select+attention) on copy 0's bytes",
+            "single_thread_us": round(t_single * 1e6, 1),
         }
         result["parity_in_bench"] = {"selection_bit_exact": sel_ok, "attn_max_abs_err": attn_err}
 

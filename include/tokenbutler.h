@@ -190,6 +190,13 @@ size_t tb_workspace_bytes(int32_t op, const tb_cache_desc* desc, int64_t max_cou
  * the same B and Hq.  Calls that overlap in time need separate workspaces. */
 tb_status tb_workspace_init(void* ws, size_t ws_bytes, void* stream);
 
+/* Measurement aid, not a step of the method: reads `bytes` (rounded down to 16) of device
+ * memory at `src` (16-byte aligned) once with plain 128-bit streaming loads and writes nothing
+ * (sink: one device word that is written only if the data fold to one particular value).  The
+ * rate it reaches is the practical read ceiling of the box for the bandwidth-bound kernels of
+ * the path, to be quoted next to the data-sheet HBM bandwidth. */
+tb_status tb_read_stream_probe(const void* src, size_t bytes, uint32_t* sink, void* stream);
+
 const char* tb_status_string(tb_status s);
 
 /* Library version: major*10000 + minor*100 + patch. */

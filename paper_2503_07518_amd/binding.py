@@ -24,7 +24,7 @@ TB_OP_SELECT, TB_OP_ATTN, TB_OP_DECODE_STEP = 1, 2, 3
 EXPORTS = (
     "tb_project_keys", "tb_score", "tb_select_topk", "tb_expand_neighbors", "tb_sparse_decode_attn",
     "tb_sparse_decode_attn_shared",
-    "tb_gather_kv", "tb_buffered_decode_attn", "tb_predict_queries", "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_status_string", "tb_version",
+    "tb_gather_kv", "tb_buffered_decode_attn", "tb_predict_queries", "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_read_stream_probe", "tb_status_string", "tb_version",
 )
 
 
@@ -80,6 +80,7 @@ def load_library() -> ctypes.CDLL:
     L.tb_workspace_bytes.argtypes = [i32, dp, i64]
     L.tb_workspace_bytes.restype = sz
     L.tb_workspace_init.argtypes = [vp, sz, vp]
+    L.tb_read_stream_probe.argtypes = [vp, sz, vp, vp]
     L.tb_status_string.argtypes = [ctypes.c_int]
     L.tb_status_string.restype = ctypes.c_char_p
     L.tb_version.restype = i32
@@ -151,6 +152,12 @@ def tb_workspace_bytes(op: int, desc: tb_cache_desc, max_count: int = 0) -> int:
 def tb_workspace_init(ws: torch.Tensor, stream=None) -> None:
     _check(load_library().tb_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
            "tb_workspace_init")
+
+
+def tb_read_stream_probe(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """Read `src` once with a plain streaming kernel (a bandwidth calibration, see the header)."""
+    _check(load_library().tb_read_stream_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
+                                               _stream(stream)), "tb_read_stream_probe")
 
 
 def new_workspace(op: int, desc: tb_cache_desc, max_count: int = 0, device="cuda") -> torch.Tensor:

@@ -411,6 +411,12 @@ tb_status tb_workspace_init(void* ws, size_t ws_bytes, void* stream) {
   return launch_fill_zero(ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
+tb_status tb_read_stream_probe(const void* src, size_t bytes, uint32_t* sink, void* stream) {
+  if (!src || !sink) return TB_ERR_INVALID_ARG;
+  if (!aligned16(src)) return TB_ERR_UNSUPPORTED;
+  return launch_read_stream(src, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
 const char* tb_status_string(tb_status s) {
   switch (s) {
     case TB_OK: return "ok";

@@ -141,6 +141,7 @@ tb_status launch_expand(int64_t units, int64_t N, int32_t radius, int32_t mode, 
                         int64_t cap_out, hipStream_t st);
 
 tb_status launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+tb_status launch_read_stream(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
 
 inline tb_status hip_status(hipError_t e) { return e == hipSuccess ? TB_OK : TB_ERR_HIP; }
 

@@ -439,3 +439,17 @@ def test_decode_step_matches_separate_calls_and_oracle(oracle, dtype, B, Hq, Hkv
     assert np.array_equal(np_of(idx)[..., : ridx.shape[-1]], ridx)
     ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K), np_of(V), np_of(idx), np_of(cnt), dn, sm)
     assert np.abs(np_of(out) - ro).max() <= ATTN_TOL[dn]
+
+
+def test_read_stream_probe_reads_and_writes_nothing():
+    """The bandwidth calibration kernel: any size (also below one vector, and ragged), the
+    source and the sink word stay as they were."""
+    from paper_2503_07518_amd import binding as tb
+    print("[case] read-stream probe", flush=True)
+    for nbytes in (8, 16, 100, 4096 * 33 + 16, 1 << 22):
+        src = torch.arange(max(nbytes, 16), dtype=torch.int64, device=DEV).to(torch.uint8)[:max(nbytes, 16)].contiguous()
+        before = src.clone()
+        sink = torch.full((4,), 7, dtype=torch.int32, device=DEV)
+        tb.tb_read_stream_probe(src[:nbytes], sink)
+        torch.cuda.synchronize()
+        assert torch.equal(src, before) and torch.all(sink == 7)
