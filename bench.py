@@ -55,8 +55,8 @@ def parse_args():
 class LayerBuffers:
     """One copy of a layer's inputs and outputs in HBM."""
 
-    def __init__(self, cfg, seed, tb, workloads, torch, kv_layout="separate", kv_host=False):
-        data = workloads.make_layer(cfg, layer=0, seed=seed, device="cuda")
+    def __init__(self, cfg, seed, tb, workloads, torch, kv_layout="separate", kv_host=False, layer=0):
+        data = workloads.make_layer(cfg, layer=layer, seed=seed, device="cuda")
         self.K, self.V, self.W = data["K"], data["V"], data["W"]
         if kv_layout == "interleaved":
             kv = torch.stack((self.K, self.V), dim=3)  # [B][Hkv][N][2][D]
@@ -478,6 +478,43 @@ def main():
         result["roofline"].update({"bound": "host_link", "peak": 64.0, "frac": round(attn_gbps / 64.0, 4),
                                    "traffic": None})
         result.pop("project_bulk")
+    if cfg.layers > 1 and not args.kv_host:
+        # the whole stack of layers, every layer with its own cache, queries and lists: one decode
+        # step of the model as far as this path goes (one graph, one step per layer)
+        del bufs[1:]
+        stack = [probe] + [LayerBuffers(cfg, 0, tb, workloads, torch, args.kv_layout, False, layer=l)
+                           for l in range(1, cfg.layers)]
+        for b in stack:
+            step(b)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for b in stack:
+                    step(b)
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(2):
+            g.replay()
+        torch.cuda.synchronize()
+        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n_rep = 10
+        d0.record()
+        for _ in range(n_rep):
+            g.replay()
+        d1.record()
+        torch.cuda.synchronize()
+        us_stack = d0.elapsed_time(d1) * 1e3 / n_rep
+        rows = sum(int(b.cnt.sum().item()) for b in stack)
+        stack_bytes = cfg.layers * bytes_kimp + rows * 2 * cfg.D * elt
+        result["depth_loop"] = {
+            "layers": cfg.layers, "us_all_layers": round(us_stack, 1), "us_per_layer": round(us_stack / cfg.layers, 3),
+            "algorithmic_bytes": stack_bytes, "achieved": round(stack_bytes / us_stack / 1e3, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(stack_bytes / us_stack / 1e3 / HBM_PEAK_GBPS, 4),
+            "resident_bytes": sum(b.nbytes() for b in stack),
+        }
+        del stack
     if cfg.P > 1:
         result["interval_loop"] = time_interval_loop(cfg, tb, workloads, torch)
         result["interval_loop_buffered"] = time_interval_loop(cfg, tb, workloads, torch, buffered=True)
