@@ -15,7 +15,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libtokenbutler.so")
-SOURCES = ["tb_api.hip", "tb_score.hip", "tb_select.hip", "tb_attn.hip", "tb_expand.hip", "tb_project.hip", "tb_gather.hip", "tb_predict.hip"]
+SOURCES = ["tb_api.hip", "tb_score.hip", "tb_select.hip", "tb_attn.hip", "tb_expand.hip", "tb_project.hip", "tb_gather.hip", "tb_predict.hip",
+           "tb_util.hip"]
 HEADERS = [os.path.join(CSRC, "tb_device.h"), os.path.join(CSRC, "tb_internal.h"),
            os.path.join(ROOT, "include", "tokenbutler.h")]
 
