@@ -13,6 +13,11 @@
 // last workgroup of a head to arrive (device-scope counter) combines the partials in split
 // order, so the result does not depend on arrival order.  The counter is reset by that
 // workgroup, which leaves the workspace ready for the next call.
+//
+// Head-less lists (one list per batch element for all heads) go through the same kernel with
+// the list shared, or, when there are enough KV groups to fill the chip, through
+// attn_group_kernel: one workgroup per (b, kv head, split) that serves all query heads of the
+// KV head, so that every listed row is loaded once.
 #include "tb_device.h"
 #include "tb_internal.h"
 
