@@ -65,7 +65,7 @@ enum { TB_OP_SELECT = 1, TB_OP_ATTN = 2, TB_OP_DECODE_STEP = 3 };
 tb_status tb_project_keys(const tb_cache_desc* desc, const void* K, const void* W, int32_t Hw, void* Kimp,
                           int64_t n_begin, int64_t n_end, void* stream);
 
-/* Importance scoring (abstract; Sec. 3.4 "score computation against all projected keys").
+/* Importance scoring (abstract; Sec. 3.4, prediction steps).
  * scores[b,h,n] = scale * sum_j q_imp[b,h,j] * K_imp[b,h/g,n,j]   for 0 <= n < desc->N.
  * q_imp: [B][Hq][Dimp] contiguous.  scores: fp32 [B][Hq][score_stride], score_stride >= N and
  * a multiple of 4.  The paper gives no normalisation of the score; `scale` is explicit. */

@@ -112,8 +112,7 @@ int tbo_project_keys(int dtype, int B, int Hkv, int64_t N, int D, int Dimp, int 
   return 0;
 }
 
-/* ---- 2. importance scoring  (abstract; Sec. 3.4: "score computation against all
- *         projected keys") ---------------------------------------------------------------- */
+/* ---- 2. importance scoring  (abstract; Sec. 3.4, prediction steps) ------------------------ */
 /* q_imp [B][Hq][Dimp], Kimp [B][Hkv][N][Dimp] -> scores fp32 [B][Hq][N]
  * query head h reads KV head h / (Hq/Hkv).                                                */
 int tbo_score(int dtype, int B, int Hq, int Hkv, int64_t N, int Dimp, const void* q_imp,

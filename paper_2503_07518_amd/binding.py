@@ -14,8 +14,7 @@ from typing import Optional, Tuple
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-# TOKENBUTLER_LIB overrides the library path (to try a differently tuned build of the same sources)
-LIB_PATH = os.environ.get("TOKENBUTLER_LIB") or os.path.join(_PKG, "libtokenbutler.so")
+LIB_PATH = os.path.join(_PKG, "libtokenbutler.so")
 
 TB_OK, TB_ERR_INVALID_ARG, TB_ERR_UNSUPPORTED, TB_ERR_WORKSPACE, TB_ERR_HIP = 0, 1, 2, 3, 4
 TB_F32, TB_BF16 = 0, 1

@@ -4,16 +4,8 @@
 
 namespace tb {
 
-#ifndef TB_ATTN_TARGET_WGS
-#define TB_ATTN_TARGET_WGS 512
-#endif
-
-#ifndef TB_GROUP_TARGET_WGS
-#define TB_GROUP_TARGET_WGS 512
-#endif
-#ifndef TB_GROUP_MIN_TILES
-#define TB_GROUP_MIN_TILES 2
-#endif
+constexpr int64_t kAttnTargetWgs = 512;   // workgroups a launch of the split attention aims at
+constexpr int64_t kAttnMinTiles = 2;      // a workgroup is worth its hand-over from two tiles per wave on
 
 AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg, bool grouped) {
   // Aim for two workgroups per compute unit (256 CUs): the gathers of the whole chip are in
@@ -27,10 +19,10 @@ AttnPlan attn_plan(int64_t units, int64_t max_rows, int tile_rows_per_wg, bool g
     p.max_split = 1;
     return p;
   }
-  const int64_t target_wgs = grouped ? TB_GROUP_TARGET_WGS : TB_ATTN_TARGET_WGS;
+  const int64_t target_wgs = kAttnTargetWgs;  // (the same for one workgroup per KV group)
   int64_t want = (target_wgs + units - 1) / units;
-  // (a workgroup is worth its hand-over from two tiles per wave on)
-  const int64_t max_split = max_rows / ((grouped ? TB_GROUP_MIN_TILES : 2) * tile_rows_per_wg);
+  (void)grouped;
+  const int64_t max_split = max_rows / (kAttnMinTiles * tile_rows_per_wg);
   if (want > max_split) want = max_split;
   if (want < 1) want = 1;
   // equal shares, rounded up to whole wave instructions (4 rows x 4 waves for 256-byte rows) rather
@@ -55,23 +47,23 @@ bool attn_shared_list_grouped(const tb_cache_desc* d) {
 }
 
 SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk) {
-  SelectPlan p{1, 0, 0};
-  // worth it when the row is long and the budget a small share of the candidates (the kept keys
-  // are then a small share of the row as well)
-  if (units <= 0 || kk <= 0 || N < 131072 || kk * 8 > candidates) return p;
-  int64_t len = 32768;
-  if (units * ((N + len - 1) / len) > 512) len = 65536;   // at most two rounds of workgroups on 256 compute units
-  // few rows (a head-less selection has one per batch element): as many pieces as the table of
-  // the second stage holds, so that more compute units take part
-  if (units * ((N + len - 1) / len) < 64) len = (((N + 15) / 16 + 4095) / 4096 * 4096 > 8192) ? ((N + 15) / 16 + 4095) / 4096 * 4096 : 8192;
+  SelectPlan p{1, 0, 0, false};
+  // worth it when the budget is a small share of the candidates (the kept keys are then a small
+  // share of the row as well) and the row is long enough to be cut
+  if (units <= 0 || kk <= 0 || N < kSelectPiecesMinN || kk * 8 > candidates) return p;
+  // pieces of 4096 << j scores (a workgroup holds up to 65536 in registers), at most 16 per row
+  // (the table of the second stage), and no more than kSelectMaxWgs workgroups in all
+  int64_t len = 4096;
+  while (len < 65536 && ((N + len - 1) / len > 16 || units * ((N + len - 1) / len) > kSelectMaxWgs)) len *= 2;
   if ((N + len - 1) / len > 16) len = ((N + 15) / 16 + 4095) / 4096 * 4096;
-  if (len > 65536) return p;                              // a piece has to fit the registers of its workgroup
+  if (len > 65536) return p;  // a piece has to fit the registers of its workgroup
   const int64_t pieces = (N + len - 1) / len;
   if (pieces < 2) return p;
   p.pieces = static_cast<int>(pieces);
   p.piece_len = len;
-  const int64_t cap = 2 * kk + 4096;                      // the budget, the bracket's slack, a coarse top bin
+  const int64_t cap = 2 * kk + 4096;  // the budget, the bracket's slack, a coarse top bin
   p.cap = ((cap < len ? cap : len) + 3) / 4 * 4;
+  p.one_launch = true;
   return p;
 }
 
@@ -221,6 +213,7 @@ tb_status tb_select_topk(const tb_cache_desc* d, const float* scores, int64_t sc
   const bool usable = ws && aligned16(ws) && ws_bytes > off;
   L.scratch = usable ? static_cast<char*>(ws) + off : nullptr;
   L.scratch_bytes = usable ? ws_bytes - off : 0;
+  L.counters = usable ? static_cast<uint32_t*>(ws) : nullptr;
   return launch_select(L, static_cast<hipStream_t>(stream));
 }
 
@@ -371,6 +364,7 @@ tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* 
   L.idx_cap = idx_cap;
   L.scratch = static_cast<char*>(ws) + w.part_off;
   L.scratch_bytes = ws_bytes - w.part_off;
+  L.counters = static_cast<uint32_t*>(ws);
   TB_TRY(launch_select(L, st));
 
   AttnLaunch A{d,   q,   K,   V,

@@ -21,16 +21,6 @@
 #include "tb_device.h"
 #include "tb_internal.h"
 
-#ifdef TB_PROBE
-__device__ unsigned long long tb_attn_probe[16];
-#define TB_AMARK(i, cond)                                                   \
-  do {                                                                      \
-    if ((cond) && threadIdx.x == 0) tb_attn_probe[i] = wall_clock64();      \
-  } while (0)
-#else
-#define TB_AMARK(i, cond)
-#endif
-
 namespace tb {
 namespace {
 
@@ -40,9 +30,7 @@ constexpr int kAttnWaves = kAttnThreads / kWave;
 constexpr int kLoadsPerTile = kAttnLoadsPerTile;
 // occupancy the register allocation is held to: 4 waves per SIMD = 4 workgroups per CU, so that a
 // launch of up to 1024 workgroups is resident at once (no second round of workgroups)
-#ifndef TB_ATTN_WAVES_PER_SIMD
-#define TB_ATTN_WAVES_PER_SIMD 4
-#endif
+constexpr int kAttnWavesPerSimd = 4;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -73,8 +61,12 @@ constexpr int32_t kTailFlag = 0x40000000;  // buffered form: the row number refe
 
 __device__ inline float exp2_safe(float d) { return __builtin_amdgcn_exp2f(d); }
 
+// Waits until every vector-memory operation this wave has issued, stores included, has been
+// acknowledged (s_waitcnt with all counters at zero).
+__device__ inline void publish_fence() { __builtin_amdgcn_s_waitcnt(0); }
+
 template <typename T, int D, bool BUF>
-__global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(kAttnThreads, kAttnWavesPerSimd) void attn_kernel(AttnArgs a) {
   constexpr int EPL = Pack16<T>::kElts;    // elements per lane
   constexpr int LPR = D / EPL;             // lanes per row
   constexpr int GPW = kWave / LPR;         // row groups per wave
@@ -113,9 +105,6 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     hkv = h / a.g;
   }
   const int64_t u = static_cast<int64_t>(b) * a.Hq + h;
-  const bool probe_wg = u == 0 && split == 0;
-  (void)probe_wg;
-  TB_AMARK(0, probe_wg);
 
   const int64_t wg_beg = static_cast<int64_t>(split) * a.rows_per_wg;
   const int rows_per_wave = a.rows_per_wg / kAttnWaves;
@@ -188,7 +177,6 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     n = n < 0 ? 0 : (n >= a.N ? a.N - 1 : n);
     n_next = (lane < TILE && i < w_end) ? static_cast<int32_t>(n) : -1;
   }
-  TB_AMARK(1, probe_wg && n_next >= -1);
   for (int64_t t0 = w_beg; t0 < w_end; t0 += TILE) {
     const int32_t n_mine = n_next;
     typename Pack16<T>::Raw kraw[kLoadsPerTile], vraw[kLoadsPerTile];  // kept packed until used
@@ -246,8 +234,6 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
       m = m_new;
     }
   }
-
-  TB_AMARK(2, probe_wg);
   // merge the row groups of the wave
 #pragma unroll
   for (int off = LPR; off < kWave; off <<= 1) {
@@ -296,26 +282,29 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
   }
 
   // Several workgroups per head: publish the partial, the last one to arrive combines.
-  // Partials are written and read with device-scope atomic accesses (they go to the memory
-  // side of the per-XCD L2 caches), so the hand-over needs no cache write-back or invalidate:
-  // the stores have completed when the barrier is passed, then the ticket is taken.
-  TB_AMARK(3, probe_wg);
+  // Partials are written and read with agent-scope accesses, which go through the L2 of the
+  // XCD to the memory side where the L2s of all XCDs meet, so the hand-over needs no cache
+  // write-back or invalidate.  Ordering: a store counts against the wave's vector-memory
+  // counter until the memory side has acknowledged it, so after publish_fence() (s_waitcnt
+  // vmcnt(0)) in every storing wave and the workgroup barrier, the partial of this workgroup is
+  // in place; only then does thread 0 issue the ticket, a read-modify-write performed at the
+  // memory side.  The drawer of the last ticket issues its agent-scope loads after the ticket
+  // has returned (branch on its value behind a barrier), so they find every partial whose
+  // ticket preceded its own.
   float* part = a.partials + (u * a.nsplit + split) * (D + 2);
   if (tid < D) __hip_atomic_store(&part[tid], o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (tid == 0) {
     __hip_atomic_store(&part[D], M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(&part[D + 1], L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  publish_fence();
   __syncthreads();
-  TB_AMARK(4, probe_wg);
   if (tid == 0) {
     const uint32_t ticket = __hip_atomic_fetch_add(&a.counters[u * kCounterStrideWords], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (ticket == static_cast<uint32_t>(a.nsplit - 1)) ? 1u : 0u;
   }
   __syncthreads();
-  TB_AMARK(5, probe_wg);
   if (!s_last) return;
-  TB_AMARK(6, u == 0);
   // Combine the partials: thread (d, lane-group j) walks splits j, j+G, ... in chunks whose
   // loads are all issued before the first is used (a dependent chain of device-scope loads
   // would cost one memory round trip per split); the G groups are then merged through LDS in
@@ -364,7 +353,6 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
       walk(std::integral_constant<int, 4>{});
     else
       walk(std::integral_constant<int, 8>{});
-    TB_AMARK(7, u == 0);
     __syncthreads();  // s_acc / s_m / s_l were last read before the partial was published
     s_acc[j][d] = og;
     if (d == 0) {
@@ -390,7 +378,6 @@ __global__ __launch_bounds__(kAttnThreads, TB_ATTN_WAVES_PER_SIMD) void attn_ker
     }
   }
   if (tid == 0) __hip_atomic_store(&a.counters[u * kCounterStrideWords], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  TB_AMARK(8, u == 0);
 }
 
 // Head-less lists with grouped queries: the GH query heads of a KV head read the same rows, so
@@ -419,9 +406,6 @@ __global__ __launch_bounds__(kAttnThreads) void attn_group_kernel(AttnArgs a) {
   const int sub = lane % LPR;
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
   const int64_t u0 = static_cast<int64_t>(b) * a.Hq + static_cast<int64_t>(hkv) * GH;  // first head of the group
-  const bool probe_wg = u0 == 0 && split == 0;
-  (void)probe_wg;
-  TB_AMARK(0, probe_wg);
 
   const int rows_per_wave = a.rows_per_wg / kAttnWaves;
   const int64_t w_beg = static_cast<int64_t>(split) * a.rows_per_wg + static_cast<int64_t>(wave) * rows_per_wave;
@@ -465,7 +449,6 @@ __global__ __launch_bounds__(kAttnThreads) void attn_group_kernel(AttnArgs a) {
     return -1;
   };
   int32_t n_next = fetch_rows(w_beg);
-  TB_AMARK(1, probe_wg && n_next >= -1);
   for (int64_t t0 = w_beg; t0 < w_end; t0 += TILE) {
     const int32_t n_mine = n_next;
     typename Pack16<T>::Raw kraw[kLoadsPerTile], vraw[kLoadsPerTile];
@@ -524,7 +507,6 @@ __global__ __launch_bounds__(kAttnThreads) void attn_group_kernel(AttnArgs a) {
   }
 
   // merge the row groups of the wave, head by head
-  TB_AMARK(2, probe_wg);
 #pragma unroll
   for (int j = 0; j < GH; ++j) {
 #pragma unroll
@@ -587,9 +569,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_group_kernel(AttnArgs a) {
     return;
   }
 
-  // several workgroups per KV group: publish the partials (device-scope accesses, as in
-  // attn_kernel), take a ticket, the last to arrive combines in split order
-  TB_AMARK(3, probe_wg);
+  // several workgroups per KV group: publish the partials (agent-scope accesses and the same
+  // ordering as in attn_kernel), take a ticket, the last to arrive combines in split order
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int e = tid + r * kAttnThreads;
@@ -603,16 +584,14 @@ __global__ __launch_bounds__(kAttnThreads) void attn_group_kernel(AttnArgs a) {
       }
     }
   }
+  publish_fence();
   __syncthreads();
-  TB_AMARK(4, probe_wg);
   if (tid == 0) {
     const uint32_t ticket = __hip_atomic_fetch_add(&a.counters[u0 * kCounterStrideWords], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (ticket == static_cast<uint32_t>(a.nsplit - 1)) ? 1u : 0u;
   }
   __syncthreads();
-  TB_AMARK(5, probe_wg);
   if (!s_last) return;
-  TB_AMARK(6, u0 == 0);
   // Combine: the device-scope loads of a chunk are issued together: per thread its R outputs
   // of CH splits; the (max, sum) pairs of those splits, the same for all elements of a head,
   // are fetched once by GH * CH threads and passed through LDS.  Splits are merged in order.
@@ -691,7 +670,6 @@ __global__ __launch_bounds__(kAttnThreads) void attn_group_kernel(AttnArgs a) {
       if (d == 0 && a.lse) a.lse[u0 + hh] = (Lg[r] > 0.f) ? Mg[r] * kLn2 + logf(Lg[r]) : -INFINITY;
     }
   }
-  TB_AMARK(8, u0 == 0);
   if (tid == 0) __hip_atomic_store(&a.counters[u0 * kCounterStrideWords], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 

@@ -11,12 +11,11 @@
 namespace tb {
 
 constexpr int64_t kSelectMaxN = 1 << 20;
+constexpr int64_t kSelectPiecesMinN = 16384;  // shorter rows are selected by one workgroup each
+constexpr int64_t kSelectMaxWgs = 1024;       // workgroups of a piecewise selection (pieces get longer beyond)
 // Arrival counters sit 256 bytes apart so that the device-scope atomics of different heads do
 // not queue up on one cache line / memory channel.
-#ifndef TB_COUNTER_STRIDE_WORDS
-#define TB_COUNTER_STRIDE_WORDS 64
-#endif
-constexpr int kCounterStrideWords = TB_COUNTER_STRIDE_WORDS;
+constexpr int kCounterStrideWords = 64;
 
 // Workspace layout (byte offsets), fixed by B*Hq so that all operations agree on it:
 //   [0, part_off)              uint32 arrival counters, one per (b,h), 256 B apart -- zero between calls
@@ -49,14 +48,17 @@ struct ScoreLaunch {
 };
 tb_status launch_score(const ScoreLaunch& a, hipStream_t st);
 
-// Long rows are selected in two stages so that several compute units work on a head: the row
+// Rows are selected in two stages when that lets several compute units work on a head: the row
 // is cut into `pieces` pieces, every piece keeps the candidates that a sample of the row puts
 // at or above the k-th largest (stage A, one workgroup per piece), and the final kk are
 // selected among the kept ones (stage B).  pieces == 1: one workgroup per row, no scratch.
+// one_launch: both stages in one kernel (the last piece of a row to finish runs stage B; needs
+// the rows' arrival counters); otherwise two kernels.
 struct SelectPlan {
   int pieces;
   int64_t piece_len;  // scores per piece (a multiple of the 4096-score workgroup tile, <= 65536)
   int64_t cap;        // kept keys a piece has room for (a multiple of 4)
+  bool one_launch;
 };
 SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk);
 // kept positions int32 and scores fp32, [units][pieces][cap] each, then int32 counts [units][pieces]
@@ -75,6 +77,8 @@ struct SelectLaunch {
   int64_t idx_cap;
   void* scratch;         // 16-byte aligned, or NULL
   size_t scratch_bytes;  // below select_scratch_bytes(): one workgroup per row is used instead
+  uint32_t* counters = nullptr;      // arrival counters of the rows (zero between calls), or NULL
+  const SelectPlan* plan = nullptr;  // NULL: select_plan() decides
 };
 tb_status launch_select(const SelectLaunch& a, hipStream_t st);
 
@@ -115,10 +119,7 @@ struct GatherLaunch {
 };
 tb_status launch_gather(const GatherLaunch& a, hipStream_t st);
 int attn_tile_rows_per_wg(int dtype, int D);
-#ifndef TB_ATTN_LOADS_PER_TILE
-#define TB_ATTN_LOADS_PER_TILE 4
-#endif
-constexpr int kAttnLoadsPerTile = TB_ATTN_LOADS_PER_TILE;  // K (and V) gathers of a lane per tile
+constexpr int kAttnLoadsPerTile = 4;  // K (and V) gathers of a lane per tile
 tb_status launch_attn(const AttnLaunch& a, hipStream_t st);
 
 // Query predictor of a producer layer (LN + two-layer MLP), see tb_predict.hip.

@@ -11,15 +11,6 @@
 #include "tb_device.h"
 #include "tb_internal.h"
 
-#ifdef TB_PROBE
-__device__ unsigned long long tb_pred_probe[16];
-#define TB_PMARK(i)                                                                              \
-  do {                                                                                           \
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) tb_pred_probe[i] = wall_clock64(); \
-  } while (0)
-#else
-#define TB_PMARK(i)
-#endif
 
 namespace tb {
 namespace {
@@ -183,8 +174,6 @@ __global__ __launch_bounds__(kPredThreads) void hidden_kernel(PredictArgs a) {
   const int b0 = blockIdx.y * BC;
   const int nb = min(BC, a.B - b0);
   const T* h = static_cast<const T*>(a.h);
-
-  TB_PMARK(0);
   // the first loads of this wave's weight row go out before the LayerNorm (they do not depend on it)
   const int r = blockIdx.x * kPredWaves + wave;       // hidden unit of this wave
   const int r_safe = r < a.hidden ? r : a.hidden - 1;
@@ -256,9 +245,7 @@ __global__ __launch_bounds__(kPredThreads) void hidden_kernel(PredictArgs a) {
   }
   for (int i = nb * e_pad + tid; i < BC * e_pad; i += kPredThreads) s_x[i] = 0.f;  // rows past the batch
   float mean[BC], rstd[BC];
-  TB_PMARK(1);
   block_sums<BC>(psum, s_red, mean);
-  TB_PMARK(2);
 #pragma unroll
   for (int bc = 0; bc < BC; ++bc) {
     mean[bc] /= static_cast<float>(a.E);
@@ -278,7 +265,6 @@ __global__ __launch_bounds__(kPredThreads) void hidden_kernel(PredictArgs a) {
     }
   }
   block_sums<BC>(psum, s_red, rstd);
-  TB_PMARK(3);
 #pragma unroll
   for (int bc = 0; bc < BC; ++bc) rstd[bc] = 1.0f / sqrtf(rstd[bc] / static_cast<float>(a.E) + a.eps);
 #pragma unroll
@@ -302,7 +288,6 @@ __global__ __launch_bounds__(kPredThreads) void hidden_kernel(PredictArgs a) {
   }
   }  // FUSED_LN
   __syncthreads();
-  TB_PMARK(4);
   if (r >= a.hidden) return;
 
   float acc[BC];
@@ -333,14 +318,12 @@ __global__ __launch_bounds__(kPredThreads) void hidden_kernel(PredictArgs a) {
     if (e0 < a.E) consume(wraw[i], e0);
   }
   for (int e0 = lane * EPL + kRowLoads * kStep; e0 < a.E; e0 += kStep) consume(Pack16<T>::load_raw(w + e0), e0);
-  TB_PMARK(5);
 #pragma unroll
   for (int bc = 0; bc < BC; ++bc) {
     const float s = wave_total(acc[bc]);
     if (lane == 0 && bc < nb)
       a.z[static_cast<int64_t>(b0 + bc) * a.hidden + r] = gelu_erf(s + to_float(static_cast<const T*>(a.b1)[r]));
   }
-  TB_PMARK(6);
 }
 
 template <typename T, int BC>

@@ -13,19 +13,10 @@
 namespace tb {
 namespace {
 
-#ifndef TB_SCORE_THREADS
-#define TB_SCORE_THREADS 256
-#endif
-#ifndef TB_SCORE_LOADS
-#define TB_SCORE_LOADS 4
-#endif
 typedef uint32_t nt_u32x4 __attribute__((ext_vector_type(4)));
-#ifndef TB_SCORE_NT_STORE_BYTES
-#define TB_SCORE_NT_STORE_BYTES (16 << 20)
-#endif
-constexpr int64_t kScoreNtStoreBytes = TB_SCORE_NT_STORE_BYTES;  // score arrays from this size on bypass the caches
-constexpr int kScoreThreads = TB_SCORE_THREADS;
-constexpr int kLoadsPerThread = TB_SCORE_LOADS;
+constexpr int64_t kScoreNtStoreBytes = 16 << 20;  // score arrays from this size on bypass the caches
+constexpr int kScoreThreads = 256;
+constexpr int kLoadsPerThread = 4;
 
 struct ScoreArgs {
   const void* q_imp;

@@ -27,16 +27,6 @@
 #include "tb_device.h"
 #include "tb_internal.h"
 
-#ifdef TB_PROBE
-__device__ unsigned long long tb_probe_buf[64];
-#define TB_MARK(i)                                                             \
-  do {                                                                         \
-    if (blockIdx.x == 0 && threadIdx.x == 0) tb_probe_buf[i] = wall_clock64(); \
-  } while (0)
-#else
-#define TB_MARK(i)
-#endif
-
 namespace tb {
 namespace {
 
@@ -70,6 +60,7 @@ struct SelectArgs {
   int32_t* cand_idx;
   float* cand_score;
   int32_t* piece_count;
+  uint32_t* arrive;  // one-launch form: the rows' arrival counters (kCounterStrideWords apart, zero between calls)
 };
 
 // A score whose key is `key` (the inverse of score_key up to the folding of NaN and -0).
@@ -84,6 +75,21 @@ __device__ inline float key_to_score(uint32_t key) {
 // keys_of4 -- which gets the unclamped position -- masks what was read.
 __device__ inline float4 load_scores4(const float* s, int64_t last4, int64_t n0) {
   return *reinterpret_cast<const float4*>(s + (n0 < last4 ? n0 : last4));
+}
+
+// Four consecutive floats (16-byte aligned) that another workgroup of the same launch has
+// written with agent-scope stores: read with agent-scope loads (two 64-bit ones), which are
+// served from the memory side of the per-XCD L2 caches and never from a stale line.
+__device__ inline float4 load_f4_agent(const float* p) {
+  const uint64_t* q = reinterpret_cast<const uint64_t*>(p);
+  const uint64_t x = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint64_t y = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  float4 f;
+  f.x = __uint_as_float(static_cast<uint32_t>(x));
+  f.y = __uint_as_float(static_cast<uint32_t>(x >> 32));
+  f.z = __uint_as_float(static_cast<uint32_t>(y));
+  f.w = __uint_as_float(static_cast<uint32_t>(y >> 32));
+  return f;
 }
 
 // Keys of the positions n0 .. n0+3.  Positions outside the candidate range [lo, hi) get key 0
@@ -125,8 +131,11 @@ struct Found {
   uint32_t extra_total;     // block-wide sum of `extra`
   uint32_t total;           // sum of all bins
   uint32_t need_a, need_b;  // the targets that were searched
+  uint32_t count_a;         // entries in bin_a (the histogram itself may be cleared for reuse once the walk is done)
+  uint32_t pad[3];
 };
-static_assert(sizeof(Found) == 32, "two 128-bit LDS reads");
+static_assert(sizeof(Found) == 48, "three 128-bit LDS reads");
+constexpr int kFoundWords = sizeof(Found) / 4;
 
 // Walk the 4096-entry LDS histogram (entries the caller does not use are 0) from the highest
 // bin down and find, for each of two targets, the bin in which the running count reaches it
@@ -175,6 +184,7 @@ __device__ inline Found find_bins(const uint32_t* s_hist, uint32_t extra, uint32
           if (t == 0) {
             s_found->bin_a = bin;
             s_found->above_a = run;
+            s_found->count_a = v;
           } else {
             s_found->bin_b = bin;
             s_found->above_b = run;
@@ -201,47 +211,67 @@ constexpr int kStreamBatch = 8;  // tiles in flight per wave while streaming
 constexpr int kMaxLevels = 4;  // bracketed level (possibly repeated once over all bins) + up to 2 levels of low bits
 
 constexpr int kMaxPieces = 16;
+constexpr int kOneLaunchStageBTiles = 8;  // one-launch form: stage B holds up to 32768 kept keys in registers
+
+// LDS of one selection (shared by the bodies that run one after the other in a kernel).
+struct SelLds {
+  uint32_t hist[2][kHistBins];  // alternating: one in use, the other being cleared
+  __attribute__((aligned(16))) Found found[kMaxLevels + 1];
+  uint32_t part[2][kSelWaves];
+  uint32_t wgt[kSelWaves], weq[kSelWaves];
+  uint32_t wabove[kSelWaves];  // streamed rows: every wave's count of keys above the bracket
+  uint32_t nlist;              // streamed rows: keys appended to the list (unusable when beyond its capacity)
+};
+// Streamed rows that keep a list: keys inside the bracket (with the wave whose span they come
+// from) and per-(counting wave, owning wave) tallies of kept / tied keys.
+struct ListLds {
+  uint32_t ckey[kListCap];
+  uint8_t cwave[kListCap];
+  uint32_t lcnt[kSelWaves][kSelWaves][2];
+};
 
 // STAGE 0: the selection of a row of scores; 2: stage B of a two-stage selection (the row is
-// what the pieces of stage A kept: `n_rows` keys read through the piece table in LDS).
+// what the pieces of stage A kept: `n_rows` keys read through the piece table in LDS); 3: the
+// same when the pieces ran in this very launch (their stores are read with agent-scope loads).
 // NT > 0: the wave's tiles are cached in registers (NT >= tiles per wave); NT == 0: the row is
-// streamed again in every phase.
-template <int NT, int STAGE>
-__device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t* s_ptab) {
-  __shared__ uint32_t s_hist[2][kHistBins];  // alternating: one in use, the other being cleared
-  __shared__ __attribute__((aligned(16))) Found s_found[kMaxLevels + 1];
-  __shared__ uint32_t s_part[2][kSelWaves];
-  __shared__ uint32_t s_wgt[kSelWaves], s_weq[kSelWaves];
-  // streamed rows only: keys inside the bracket (with the wave whose span they come from), the
-  // number appended (the list is unusable when it exceeds the capacity), every wave's count of
-  // keys above the bracket, and per-(counting wave, owning wave) tallies of kept / tied keys
-  constexpr bool kStream = NT == 0;
-  __shared__ uint32_t s_ckey[kStream ? kListCap : 1];
-  __shared__ uint8_t s_cwave[kStream ? kListCap : 4];
-  __shared__ uint32_t s_nlist;
-  __shared__ uint32_t s_wabove[kSelWaves];
-  __shared__ uint32_t s_lcnt[kStream ? kSelWaves : 1][kSelWaves][2];
+// streamed again in every phase; with a list (ll != nullptr) the keys inside the bracket are
+// kept in LDS and only two passes read the scores.
+// u: the row (b*Hq + h) this workgroup selects for.
+template <int NT, int STAGE, bool LIST = (NT == 0)>
+__device__ __forceinline__ void select_body(const SelectArgs& a, const int u, const uint32_t* s_ptab, SelLds& sl,
+                                            ListLds* ll) {
+  static_assert(!LIST || NT == 0, "only streamed rows keep a list");
+  constexpr bool kStream = LIST;
+  constexpr bool kStageB = STAGE >= 2;   // the row is what the pieces kept
+  constexpr bool kAgent = STAGE == 3;    // ... written by other workgroups of this launch: agent-scope loads
+  uint32_t (&s_hist)[2][kHistBins] = sl.hist;
+  Found (&s_found)[kMaxLevels + 1] = sl.found;
+  uint32_t (&s_part)[2][kSelWaves] = sl.part;
+  uint32_t (&s_wgt)[kSelWaves] = sl.wgt;
+  uint32_t (&s_weq)[kSelWaves] = sl.weq;
+  uint32_t (&s_wabove)[kSelWaves] = sl.wabove;
+  uint32_t& s_nlist = sl.nlist;
+  uint32_t* s_ckey = kStream ? ll->ckey : nullptr;
+  uint8_t* s_cwave = kStream ? ll->cwave : nullptr;
+  uint32_t (*s_lcnt)[kSelWaves][2] = kStream ? ll->lcnt : nullptr;
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = tid / kWave;
-  const int u = blockIdx.x;
   const int kk = a.kk;
   // stage B: the row is the concatenation of the pieces' kept keys, every piece padded to a
   // multiple of 4 (s_ptab[c] = where piece c starts in it, s_ptab[kMaxPieces] = its length,
   // s_ptab[kMaxPieces + 1 + c] = keys in piece c); every key of it is a candidate
-  const int64_t N = STAGE == 2 ? static_cast<int64_t>(s_ptab[kMaxPieces]) : a.N;
-  const int lo = STAGE == 2 ? 0 : a.lo, hi = STAGE == 2 ? static_cast<int>(N) : a.hi;
-  const float* s = STAGE == 2 ? a.cand_score + static_cast<int64_t>(u) * a.pieces * a.cap
+  const int64_t N = kStageB ? static_cast<int64_t>(s_ptab[kMaxPieces]) : a.N;
+  const int lo = kStageB ? 0 : a.lo, hi = kStageB ? static_cast<int>(N) : a.hi;
+  const float* s = kStageB ? a.cand_score + static_cast<int64_t>(u) * a.pieces * a.cap
                               : a.scores + static_cast<int64_t>(u) * a.score_stride;
   int32_t* out = a.idx + static_cast<int64_t>(u) * a.idx_cap;
   // stage B: as many tiles per wave as the row needs (its length is not known at launch)
   const int tpw_b = static_cast<int>((N + kTileElts - 1) / kTileElts);
-  const int tpw = (NT > 0) ? (STAGE == 2 ? (tpw_b < 1 ? 1 : (tpw_b < NT ? tpw_b : NT)) : NT) : a.tiles_per_wave;
+  const int tpw = (NT > 0) ? (kStageB ? (tpw_b < 1 ? 1 : (tpw_b < NT ? tpw_b : NT)) : NT) : a.tiles_per_wave;
   const int64_t wbase = static_cast<int64_t>(wave) * tpw * kWaveTile + lane * 4;
   const bool refine = kk > 0 && kk < hi - lo;
-
-  TB_MARK(0);
   const int64_t last4 = N > 0 ? ((N - 1) & ~int64_t{3}) : 0;  // the vector that holds the last score
   // stage B: where position n (a multiple of 4) of the row lies in the [piece][cap] arrays, and
   // how many of the four keys from there on are real (the rest is padding)
@@ -256,14 +286,14 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
   uint32_t keys[NT > 0 ? NT : 1][4];
   if (NT > 0 && kk > 0) {
     float4 raw[NT > 0 ? NT : 1];  // every load of the thread is issued before the first is used
-    if constexpr (STAGE == 2) {
+    if constexpr (kStageB) {
       int valid[NT > 0 ? NT : 1];
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int64_t n0 = wbase + j * kWaveTile;
         valid[j] = 0;
         const int64_t phys = (j < tpw && n0 < N) ? locate(n0, valid[j]) : 0;
-        raw[j] = *reinterpret_cast<const float4*>(s + phys);
+        raw[j] = kAgent ? load_f4_agent(s + phys) : *reinterpret_cast<const float4*>(s + phys);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -281,7 +311,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
     }
   }
   for (int i = tid; i < 2 * kHistBins; i += kSelThreads) (&s_hist[0][0])[i] = 0;
-  if (tid < (kMaxLevels + 1) * 8) reinterpret_cast<uint32_t*>(s_found)[tid] = 0;
+  if (tid < (kMaxLevels + 1) * kFoundWords) reinterpret_cast<uint32_t*>(&s_found[0])[tid] = 0;
   if (tid == 0) s_nlist = 0;
 
   // always-kept ranges: sink prefix [0, lo) and local window [hi, N) of the original row
@@ -290,7 +320,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
   for (int64_t n = a.hi + tid; n < a.N; n += kSelThreads) out[a.lo + kk + (n - a.hi)] = static_cast<int32_t>(n);
   if (tid == 0) a.count[u] = static_cast<int32_t>(a.lo + kk + (a.N - a.hi));
   int32_t* sel_out = out + a.lo;
-  const int32_t* remap = STAGE == 2 ? a.cand_idx + static_cast<int64_t>(u) * a.pieces * a.cap : nullptr;
+  const int32_t* remap = kStageB ? a.cand_idx + static_cast<int64_t>(u) * a.pieces * a.cap : nullptr;
   if (kk == 0) return;
 
   // visit every tile of this wave's span: body(j, keys of the tile)
@@ -298,7 +328,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
     if constexpr (NT > 0) {
 #pragma unroll
       for (int j = 0; j < NT; ++j)
-        if (STAGE != 2 || j < tpw) body(j, keys[j]);
+        if (!kStageB || j < tpw) body(j, keys[j]);
     } else {
       // streamed: the loads of kStreamBatch tiles are issued before the first tile is used (one
       // load per iteration would leave a wave with 1 KiB in flight and the pass latency-bound)
@@ -325,7 +355,6 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
   bool list_ok = false;  // streamed rows: the LDS list holds every key inside the bracket
   if (refine) {
     __syncthreads();  // LDS initialised
-    TB_MARK(1);
     // ---- bracket from a sample: the first key of (up to) four tiles per thread
     constexpr int kSamples = (NT > 0 && NT < 4) ? NT : 4;
     uint32_t n_valid = 0;
@@ -339,7 +368,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
     for (int i = 0; i < kSamples; ++i) {
       uint32_t ks;
       if constexpr (NT > 0) {
-        ks = keys[STAGE == 2 ? i : (i * NT) / kSamples][0];  // (stage B: the row may end after a few tiles)
+        ks = keys[kStageB ? i : (i * NT) / kSamples][0];  // (stage B: the row may end after a few tiles)
       } else {
         uint32_t k4[4];
         keys_of4(sraw[i], lo, hi, wbase + static_cast<int64_t>((i * tpw) / kSamples) * kWaveTile, k4);
@@ -364,19 +393,17 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
     uint32_t b_lo = (fb.need_b <= fb.extra_total) ? fb.bin_b : 1u;     // bottom bin of the bracket
     if (b_lo < 1u) b_lo = 1u;                                   // bin 0 holds only "not a candidate"
     if (b_hi < b_lo) b_hi = b_lo;
-    TB_MARK(2);
 
     // ---- radix descent.  Level state: candidates are the keys with lo_key <= key < lo_key +
     // span, histogrammed by (key - lo_key) >> shift; keys above `above_key` (only on the
     // first, bracketed level) are counted instead.  If the exact counts of the first level
     // show that T is not inside the bracket, the level is repeated over every real bin.
-    uint32_t lo_key, span, above_key, nbins, need = static_cast<uint32_t>(kk);
+    uint32_t lo_key, span, above_key, need = static_cast<uint32_t>(kk);
     int shift;
     {
       const uint32_t nb = b_hi - b_lo + 1;                         // 12-bit bins in the bracket
       const int e = 31 - __clz(static_cast<int>(kHistBins / nb));  // extra bits of resolution
       shift = kTopShift - e;
-      nbins = nb << e;
       lo_key = b_lo << kTopShift;
       span = nb << kTopShift;
       above_key = (b_hi == kHistBins - 1) ? 0xFFFFFFFFu : ((b_hi + 1) << kTopShift) - 1u;
@@ -431,7 +458,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
             if (d < span) atomicAdd(&h[d >> shift], 1u);
           }
         });
-      } else if (list_ok) {
+      } else if (kStream && list_ok) {
         // streamed row: the keys of the chosen sub-bin are all in the LDS list
         const uint32_t nl = s_nlist;
         for (uint32_t i = tid; i < nl; i += kSelThreads) {
@@ -451,7 +478,6 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
           }
         });
       }
-      TB_MARK(8 + 4 * call);
       // clear the other histogram for the next level while this one is being filled
       for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[cur ^ 1][i] = 0;
       const Found f = find_bins(h, n_above, s_part[call & 1], &s_found[call], [&](uint32_t c_above, uint32_t& na, uint32_t& nb) {
@@ -463,19 +489,17 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
         list_ok = s_nlist <= static_cast<uint32_t>(kListCap);
         if (tid < kSelWaves) s_wabove[tid] = s_part[1][tid];  // per-wave counts of keys above the bracket
       }
-      TB_MARK(10 + 4 * call);
       cur ^= 1;
       if (want >= 1u && want <= total_in) {  // T lies inside this level's range: descend
         lo_key += f.bin_a << shift;
         need = want - f.above_a;
         if (shift == 0) break;
-        if (need == h[f.bin_a]) {
+        if (need == f.count_a) {
           // every key of this sub-bin is needed: no reason to look at its low bits
           take_whole_bin = true;
           break;
         }
         const int nshift = shift > 12 ? shift - 12 : 0;
-        nbins = 1u << (shift - nshift);
         span = 1u << shift;
         shift = nshift;
         above_key = 0xFFFFFFFFu;
@@ -486,19 +510,16 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
         lo_key = 1u << kTopShift;
         span = static_cast<uint32_t>(kHistBins - 1) << kTopShift;
         shift = kTopShift;
-        nbins = kHistBins - 1;
         above_key = 0xFFFFFFFFu;
         list_ok = false;
       }
     }
-    TB_MARK(3);
     T = lo_key;
     r_eq = need;
     if (take_whole_bin) {  // keep everything from the start of the sub-bin upwards
       T = lo_key - 1u;
       r_eq = 0u;
     }
-    TB_MARK(4);
   }
   // kk == hi - lo: T = 0 keeps every candidate (all real keys are > 0)
 
@@ -512,7 +533,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
   };
   constexpr bool kKeepPre = NT > 0 && NT <= 8;  // keep the in-tile prefixes when registers allow
   uint32_t pre[kKeepPre ? NT : 1];
-  if (list_ok) {
+  if (kStream && list_ok) {
     // streamed row: the per-wave totals come from the list instead of another pass over the
     // scores (a key above the bracket is kept for sure; a key below it never is)
     for (int i = tid; i < (kStream ? kSelWaves : 1) * kSelWaves * 2; i += kSelThreads) (&s_lcnt[0][0][0])[i] = 0;
@@ -553,7 +574,6 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
     }
   }
   __syncthreads();
-  TB_MARK(5);
   // kept / tied keys in the spans of the waves before this one
   uint32_t unused_total;
   uint32_t base_gt = wave_entries_scan(s_wgt, unused_total);
@@ -564,7 +584,9 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
   auto emit = [&](uint32_t pos, int32_t n, int c) {
     if (pos < static_cast<uint32_t>(kk)) {
       if constexpr (STAGE == 0) sel_out[pos] = n + c;
-      if constexpr (STAGE == 2) sel_out[pos] = remap[tile_phys + c];  // position in the original row
+      if constexpr (kStageB)  // position in the original row
+        sel_out[pos] = kAgent ? __hip_atomic_load(&remap[tile_phys + c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                              : remap[tile_phys + c];
     }
   };
   for_each_tile([&](int j, const uint32_t(&k4)[4]) {
@@ -579,7 +601,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
     uint32_t gt_before = base_gt + (excl & 0xFFFFu);
     uint32_t eq_before = base_eq + (excl >> 16);
     const int32_t nn = static_cast<int32_t>(wbase + static_cast<int64_t>(j) * kWaveTile);
-    if constexpr (STAGE == 2) {
+    if constexpr (kStageB) {
       int valid;
       tile_phys = nn < N ? locate(nn, valid) : 0;
     }
@@ -608,28 +630,34 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const uint32_t*
     base_gt += tot & 0xFFFFu;
     base_eq += tot >> 16;
   });
-  TB_MARK(6);
 }
 
 template <int NT>
 __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void select_kernel(SelectArgs a) {
-  select_body<NT, 0>(a, nullptr);
+  __shared__ SelLds sl;
+  if constexpr (NT == 0) {
+    __shared__ ListLds ll;
+    select_body<0, 0>(a, blockIdx.x, nullptr, sl, &ll);
+  } else {
+    select_body<NT, 0>(a, blockIdx.x, nullptr, sl, nullptr);
+  }
 }
 
-// ---- two-stage selection, stage A.  One workgroup per (row, piece); the piece's keys stay in
-// registers (NT tiles per wave, piece_len <= 65536).  Every piece of a row takes the same
-// sample of the row's candidates (4096 positions spread over [lo, hi)) and so arrives at the
-// same threshold: the lower end of the bracket that the one-workgroup selection would use.
-template <int NT>
-__global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void prefilter_kernel(SelectArgs a) {
-  __shared__ uint32_t s_hist[kHistBins];
-  __shared__ __attribute__((aligned(16))) Found s_found;
-  __shared__ uint32_t s_part[kSelWaves];
-  __shared__ uint32_t s_wcnt[kSelWaves];
+// ---- selection of a row by several workgroups, stage A.  One workgroup per (row, piece); the
+// piece's keys stay in registers (NT tiles per wave, piece_len <= 65536).  Every piece of a row
+// takes the same sample of the row's candidates (4096 positions spread over [lo, hi)) and so
+// arrives at the same threshold: the lower end of the bracket that the one-workgroup selection
+// would use.  AGENT: the kept keys are read by another workgroup of the same launch, so they
+// are written with agent-scope stores (through the L2 of this XCD).
+template <int NT, bool AGENT>
+__device__ __forceinline__ void prefilter_body(const SelectArgs& a, const int u, const int c, SelLds& sl) {
+  uint32_t* s_hist = sl.hist[0];
+  Found& s_found = sl.found[0];
+  uint32_t* s_part = sl.part[0];
+  uint32_t* s_wcnt = sl.wgt;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = tid / kWave;
-  const int u = blockIdx.x / a.pieces, c = blockIdx.x % a.pieces;
   const int64_t base = c * a.piece_len;
   int64_t n_c = a.N - base;
   n_c = n_c < 0 ? 0 : (n_c > a.piece_len ? a.piece_len : n_c);
@@ -640,8 +668,6 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void pre
   const float* s = row + base;
   const int64_t last4 = n_c > 0 ? ((n_c - 1) & ~int64_t{3}) : 0;
   const int64_t wbase = static_cast<int64_t>(wave) * NT * kWaveTile + lane * 4;
-
-  TB_MARK(20);
   // the sample of the whole row: 256 clusters of 16 adjacent scores (one 64-byte line each, so
   // that sampling does not pull the whole row through the caches once more), spread evenly over
   // the candidates; four threads share a cluster with one 128-bit load each
@@ -663,9 +689,8 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void pre
   }
 
   for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
-  if (tid < 8) reinterpret_cast<uint32_t*>(&s_found)[tid] = 0;
+  if (tid < kFoundWords) reinterpret_cast<uint32_t*>(&s_found)[tid] = 0;
   __syncthreads();
-  TB_MARK(21);
   uint32_t n_valid = 0;
   {
     uint32_t sk[4];
@@ -678,7 +703,6 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void pre
       }
     }
   }
-  TB_MARK(22);
   const int kk = a.kk;
   const Found fb = find_bins(s_hist, n_valid, s_part, &s_found, [&](uint32_t n_s, uint32_t& na, uint32_t& nb) {
     const float frac = static_cast<float>(kk) / static_cast<float>(span);
@@ -691,7 +715,6 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void pre
   uint32_t b_lo = (fb.need_b <= fb.extra_total) ? fb.bin_b : 1u;
   if (b_lo < 1u) b_lo = 1u;
   const uint32_t t_lo = b_lo << kTopShift;  // keys from here up are kept
-  TB_MARK(23);
 
   // ordered compaction of the piece's kept keys (prefix sums as in the selection itself)
   uint32_t pre[NT];
@@ -707,12 +730,17 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void pre
   }
   if (lane == 0) s_wcnt[wave] = run;
   __syncthreads();
-  TB_MARK(24);
   uint32_t total;
   const uint32_t wave_base = wave_entries_scan(s_wcnt, total);
-  if (tid == 0) a.piece_count[static_cast<int64_t>(u) * a.pieces + c] = static_cast<int32_t>(total);
   int32_t* out_idx = a.cand_idx + (static_cast<int64_t>(u) * a.pieces + c) * a.cap;
   float* out_score = a.cand_score + (static_cast<int64_t>(u) * a.pieces + c) * a.cap;
+  int32_t* out_count = a.piece_count + static_cast<int64_t>(u) * a.pieces + c;
+  if (tid == 0) {
+    if (AGENT)
+      __hip_atomic_store(out_count, static_cast<int32_t>(total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+      *out_count = static_cast<int32_t>(total);
+  }
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
     uint32_t pos = wave_base + pre[j];
@@ -720,47 +748,108 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void pre
     for (int e = 0; e < 4; ++e) {
       if (keys[j][e] >= t_lo) {
         if (pos < static_cast<uint32_t>(a.cap)) {
-          out_idx[pos] = static_cast<int32_t>(base + wbase + j * kWaveTile + e);
-          out_score[pos] = key_to_score(keys[j][e]);  // same key again in stage B
+          const int32_t n = static_cast<int32_t>(base + wbase + j * kWaveTile + e);
+          const float sc = key_to_score(keys[j][e]);  // same key again in stage B
+          if (AGENT) {
+            __hip_atomic_store(&out_idx[pos], n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&out_score[pos], sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          } else {
+            out_idx[pos] = n;
+            out_score[pos] = sc;
+          }
         }
         ++pos;
       }
     }
   }
-  TB_MARK(25);
 }
 
 // ---- stage B.  One workgroup per row: builds the table of the pieces' kept keys and selects
-// among them, or -- when the pieces kept fewer than kk keys or one of them overflowed -- selects
-// on the original row (one streaming workgroup: slow, but it only happens when the sample of
-// stage A was wildly unrepresentative).
-template <int NT>
-__global__ __launch_bounds__(kSelThreads, 4) void stage_b_kernel(SelectArgs a) {
-  __shared__ uint32_t s_ptab[2 * kMaxPieces + 2];
-  __shared__ uint32_t s_ok;
-  TB_MARK(29);
-  if (threadIdx.x == 0) {
-    const int32_t* cnt = a.piece_count + static_cast<int64_t>(blockIdx.x) * a.pieces;
-    uint32_t at = 0, kept = 0, ok = 1;
-    for (int c = 0; c < kMaxPieces; ++c) {
-      const uint32_t n = c < a.pieces ? static_cast<uint32_t>(cnt[c]) : 0u;
-      if (n > static_cast<uint32_t>(a.cap)) ok = 0;
-      s_ptab[c] = at;
-      s_ptab[kMaxPieces + 1 + c] = n;
-      at += (n + 3u) & ~3u;
-      kept += n;
+// among them, or -- when the pieces kept fewer than kk keys, one of them overflowed, or they kept
+// more than this instance holds in registers -- selects on the original row (one streaming
+// workgroup: slow, but it only happens when the sample of stage A was wildly unrepresentative).
+// s_ptab: 2 * kMaxPieces + 3 words.
+template <int NT, bool AGENT>
+__device__ __forceinline__ void stage_b_body(const SelectArgs& a, const int u, SelLds& sl, ListLds* ll,
+                                             uint32_t* s_ptab) {
+  const int tid = threadIdx.x;
+  if (tid < kWave) {  // wave 0: one lane per piece
+    const int32_t* cnt = a.piece_count + static_cast<int64_t>(u) * a.pieces;
+    uint32_t n = 0;
+    if (tid < a.pieces)
+      n = static_cast<uint32_t>(AGENT ? __hip_atomic_load(&cnt[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                      : cnt[tid]);
+    const uint32_t padded = (n + 3u) & ~3u;
+    const uint32_t incl_p = wave_incl_scan_u32(padded);
+    const uint32_t incl_n = wave_incl_scan_u32(n);
+    const unsigned long long over = __ballot(n > static_cast<uint32_t>(a.cap));
+    if (tid < kMaxPieces) {
+      s_ptab[tid] = incl_p - padded;
+      s_ptab[kMaxPieces + 1 + tid] = n;
     }
-    s_ptab[kMaxPieces] = at;
-    if (at > static_cast<uint32_t>(NT * kTileElts)) ok = 0;  // more than this instance holds in registers
-    s_ok = (ok && kept >= static_cast<uint32_t>(a.kk)) ? 1u : 0u;
+    if (tid == kWave - 1) {
+      s_ptab[kMaxPieces] = incl_p;  // length of the row of kept keys
+      const bool ok = !over && incl_p <= static_cast<uint32_t>(NT * kTileElts) && incl_n >= static_cast<uint32_t>(a.kk);
+      s_ptab[2 * kMaxPieces + 2] = ok ? 1u : 0u;
+    }
   }
   __syncthreads();
-  TB_MARK(30);
-  if (s_ok) {
-    select_body<NT, 2>(a, s_ptab);
+  if (s_ptab[2 * kMaxPieces + 2]) {
+    select_body<NT, AGENT ? 3 : 2>(a, u, s_ptab, sl, nullptr);
+  } else if (ll) {
+    select_body<0, 0, true>(a, u, nullptr, sl, ll);
   } else {
-    select_body<0, 0>(a, nullptr);
+    select_body<0, 0, false>(a, u, nullptr, sl, nullptr);
   }
+}
+
+template <int NT>
+__global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void prefilter_kernel(SelectArgs a) {
+  __shared__ SelLds sl;
+  prefilter_body<NT, false>(a, blockIdx.x / a.pieces, blockIdx.x % a.pieces, sl);
+}
+
+template <int NT>
+__global__ __launch_bounds__(kSelThreads, 4) void stage_b_kernel(SelectArgs a) {
+  __shared__ SelLds sl;
+  __shared__ ListLds ll;
+  __shared__ uint32_t s_ptab[2 * kMaxPieces + 3];
+  stage_b_body<NT, false>(a, blockIdx.x, sl, &ll, s_ptab);
+}
+
+// ---- both stages in one launch.  The pieces of a row publish what they kept with agent-scope
+// stores, wait until those stores have been acknowledged, and take a ticket from the row's
+// arrival counter; the piece that draws the last ticket runs stage B for the row and puts the
+// counter back to zero.
+//
+// Why the last piece sees the others' data.  Agent-scope stores are written through the L2 of
+// the storing XCD to the memory side, where the L2s of all XCDs meet; a store counts against
+// the wave's vector-memory counter until that write is acknowledged, so after `s_waitcnt
+// vmcnt(0)` in every storing wave and the workgroup barrier, all stores of the workgroup have
+// reached the memory side.  Only then does thread 0 issue the ticket, a read-modify-write that
+// is itself performed at the memory side and hence ordered there after the stores of every
+// piece whose ticket precedes it.  The drawer of the last ticket issues its agent-scope loads
+// after the ticket has returned (they depend on it through the branch and a barrier); such
+// loads bypass the L2 lines of the reading XCD, so they return the acknowledged data.
+template <int NTA, int NTB>
+__global__ __launch_bounds__(kSelThreads, 4) void select_pieces_kernel(SelectArgs a) {
+  __shared__ SelLds sl;
+  __shared__ uint32_t s_ptab[2 * kMaxPieces + 3];
+  __shared__ uint32_t s_last;
+  const int u = blockIdx.x / a.pieces, c = blockIdx.x % a.pieces;
+  prefilter_body<NTA, true>(a, u, c, sl);
+  __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0): this wave's agent-scope stores have been acknowledged
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t* counter = a.arrive + static_cast<int64_t>(u) * kCounterStrideWords;
+    const uint32_t ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = ticket == static_cast<uint32_t>(a.pieces - 1);
+    if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
+    s_last = last ? 1u : 0u;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  stage_b_body<NTB, true>(a, u, sl, nullptr, s_ptab);
 }
 
 }  // namespace
@@ -809,7 +898,8 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   a.cand_idx = nullptr;
   a.cand_score = nullptr;
   a.piece_count = nullptr;
-  const SelectPlan plan = select_plan(L.units, L.hi - L.lo, L.N, L.kk);
+  a.arrive = L.counters;
+  const SelectPlan plan = L.plan ? *L.plan : select_plan(L.units, L.hi - L.lo, L.N, L.kk);
   if (plan.pieces <= 1 || !L.scratch || L.scratch_bytes < select_scratch_bytes(L.units, plan))
     return launch_whole(a, L.units, st);
 
@@ -823,19 +913,33 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   a.piece_count = reinterpret_cast<int32_t*>(a.cand_score + L.units * per_unit);
   a.tiles_per_wave = static_cast<int32_t>((L.N + kTileElts - 1) / kTileElts);  // for the fall-back on the whole row
   dim3 block(kSelThreads);
-  {
-    dim3 grid(static_cast<unsigned>(L.units * plan.pieces));
-    const int tiles = static_cast<int>((plan.piece_len + kTileElts - 1) / kTileElts);
-    if (tiles <= 1)
-      hipLaunchKernelGGL(prefilter_kernel<1>, grid, block, 0, st, a);
-    else if (tiles <= 2)
-      hipLaunchKernelGGL(prefilter_kernel<2>, grid, block, 0, st, a);
-    else if (tiles <= 4)
-      hipLaunchKernelGGL(prefilter_kernel<4>, grid, block, 0, st, a);
-    else if (tiles <= 8)
-      hipLaunchKernelGGL(prefilter_kernel<8>, grid, block, 0, st, a);
+  const dim3 grid_a(static_cast<unsigned>(L.units * plan.pieces));
+  const int tiles_a = static_cast<int>((plan.piece_len + kTileElts - 1) / kTileElts);
+  if (plan.one_launch && L.counters) {
+    constexpr int NTB = kOneLaunchStageBTiles;
+    if (tiles_a <= 1)
+      hipLaunchKernelGGL((select_pieces_kernel<1, NTB>), grid_a, block, 0, st, a);
+    else if (tiles_a <= 2)
+      hipLaunchKernelGGL((select_pieces_kernel<2, NTB>), grid_a, block, 0, st, a);
+    else if (tiles_a <= 4)
+      hipLaunchKernelGGL((select_pieces_kernel<4, NTB>), grid_a, block, 0, st, a);
+    else if (tiles_a <= 8)
+      hipLaunchKernelGGL((select_pieces_kernel<8, NTB>), grid_a, block, 0, st, a);
     else
-      hipLaunchKernelGGL(prefilter_kernel<16>, grid, block, 0, st, a);
+      hipLaunchKernelGGL((select_pieces_kernel<16, NTB>), grid_a, block, 0, st, a);
+    return hip_status(hipGetLastError());
+  }
+  {
+    if (tiles_a <= 1)
+      hipLaunchKernelGGL(prefilter_kernel<1>, grid_a, block, 0, st, a);
+    else if (tiles_a <= 2)
+      hipLaunchKernelGGL(prefilter_kernel<2>, grid_a, block, 0, st, a);
+    else if (tiles_a <= 4)
+      hipLaunchKernelGGL(prefilter_kernel<4>, grid_a, block, 0, st, a);
+    else if (tiles_a <= 8)
+      hipLaunchKernelGGL(prefilter_kernel<8>, grid_a, block, 0, st, a);
+    else
+      hipLaunchKernelGGL(prefilter_kernel<16>, grid_a, block, 0, st, a);
     if (hipGetLastError() != hipSuccess) return TB_ERR_HIP;
   }
   {
