@@ -47,23 +47,26 @@ bool attn_shared_list_grouped(const tb_cache_desc* d) {
 }
 
 SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk) {
-  SelectPlan p{1, 0, 0, false};
-  // worth it when the budget is a small share of the candidates (the kept keys are then a small
-  // share of the row as well) and the row is long enough to be cut
-  if (units <= 0 || kk <= 0 || N < kSelectPiecesMinN || kk * 8 > candidates) return p;
-  // pieces of 4096 << j scores (a workgroup holds up to 65536 in registers), at most 16 per row
-  // (the table of the second stage), and no more than kSelectMaxWgs workgroups in all
-  int64_t len = 4096;
-  while (len < 65536 && ((N + len - 1) / len > 16 || units * ((N + len - 1) / len) > kSelectMaxWgs)) len *= 2;
+  SelectPlan p{1, 0, 0, 2};
+  // worth it when the row is long and the budget a small share of the candidates (the kept keys
+  // are then a small share of the row as well); measured on 16K..64K rows, two launches cost
+  // more than the one-workgroup selection
+  if (units <= 0 || kk <= 0 || N < 131072 || kk * 8 > candidates) return p;
+  int64_t len = 32768;
+  if (units * ((N + len - 1) / len) > 512) len = 65536;   // at most two rounds of workgroups on 256 compute units
+  // few rows (a head-less selection has one per batch element): more, shorter pieces, so that
+  // more compute units take part
+  if (units * ((N + len - 1) / len) < 64) len = (((N + 15) / 16 + 4095) / 4096 * 4096 > 8192) ? ((N + 15) / 16 + 4095) / 4096 * 4096 : 8192;
   if ((N + len - 1) / len > 16) len = ((N + 15) / 16 + 4095) / 4096 * 4096;
-  if (len > 65536) return p;  // a piece has to fit the registers of its workgroup
+  if (len > 65536) return p;                              // a piece has to fit the registers of its workgroup
   const int64_t pieces = (N + len - 1) / len;
   if (pieces < 2) return p;
   p.pieces = static_cast<int>(pieces);
   p.piece_len = len;
-  const int64_t cap = 2 * kk + 4096;  // the budget, the bracket's slack, a coarse top bin
+  const int64_t cap = 2 * kk + 4096;                      // the budget, the bracket's slack, a coarse top bin
   p.cap = ((cap < len ? cap : len) + 3) / 4 * 4;
-  p.one_launch = true;
+  const int64_t tiles = (pieces * p.cap + 4095) / 4096;   // at most: the pieces' capacity
+  p.stage_b_tiles = tiles <= 2 ? 2 : (tiles <= 4 ? 4 : (tiles <= 8 ? 8 : 16));
   return p;
 }
 
@@ -213,7 +216,6 @@ tb_status tb_select_topk(const tb_cache_desc* d, const float* scores, int64_t sc
   const bool usable = ws && aligned16(ws) && ws_bytes > off;
   L.scratch = usable ? static_cast<char*>(ws) + off : nullptr;
   L.scratch_bytes = usable ? ws_bytes - off : 0;
-  L.counters = usable ? static_cast<uint32_t*>(ws) : nullptr;
   return launch_select(L, static_cast<hipStream_t>(stream));
 }
 
@@ -364,7 +366,6 @@ tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* 
   L.idx_cap = idx_cap;
   L.scratch = static_cast<char*>(ws) + w.part_off;
   L.scratch_bytes = ws_bytes - w.part_off;
-  L.counters = static_cast<uint32_t*>(ws);
   TB_TRY(launch_select(L, st));
 
   AttnLaunch A{d,   q,   K,   V,

@@ -11,8 +11,6 @@
 namespace tb {
 
 constexpr int64_t kSelectMaxN = 1 << 20;
-constexpr int64_t kSelectPiecesMinN = 16384;  // shorter rows are selected by one workgroup each
-constexpr int64_t kSelectMaxWgs = 1024;       // workgroups of a piecewise selection (pieces get longer beyond)
 // Arrival counters sit 256 bytes apart so that the device-scope atomics of different heads do
 // not queue up on one cache line / memory channel.
 constexpr int kCounterStrideWords = 64;
@@ -48,22 +46,22 @@ struct ScoreLaunch {
 };
 tb_status launch_score(const ScoreLaunch& a, hipStream_t st);
 
-// Rows are selected in two stages when that lets several compute units work on a head: the row
+// Long rows are selected in two stages so that several compute units work on a head: the row
 // is cut into `pieces` pieces, every piece keeps the candidates that a sample of the row puts
 // at or above the k-th largest (stage A, one workgroup per piece), and the final kk are
-// selected among the kept ones (stage B).  pieces == 1: one workgroup per row, no scratch.
-// one_launch: both stages in one kernel (the last piece of a row to finish runs stage B; needs
-// the rows' arrival counters); otherwise two kernels.
+// selected among the kept ones (stage B, a second kernel).  pieces == 1: one workgroup per row,
+// no scratch.  The same plan describes the kept keys that the scoring kernel leaves behind when
+// it runs stage A itself (one piece per tile of rows it scores).
 struct SelectPlan {
   int pieces;
-  int64_t piece_len;  // scores per piece (a multiple of the 4096-score workgroup tile, <= 65536)
+  int64_t piece_len;  // scores per piece
   int64_t cap;        // kept keys a piece has room for (a multiple of 4)
-  bool one_launch;
+  int stage_b_tiles;  // 4096-key tiles of kept keys that stage B holds in registers: 2, 4, 8 or 16
 };
 SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk);
-// kept positions int32 and scores fp32, [units][pieces][cap] each, then int32 counts [units][pieces]
+// kept positions int32 and keys uint32, [units][pieces][cap] each, then 4 words of header per piece
 inline size_t select_scratch_bytes(int64_t units, const SelectPlan& p) {
-  return p.pieces > 1 ? static_cast<size_t>(units) * p.pieces * (p.cap * 8 + 4) : 0;
+  return p.pieces > 1 ? static_cast<size_t>(units) * p.pieces * (p.cap * 8 + 16) : 0;
 }
 
 struct SelectLaunch {
@@ -77,10 +75,11 @@ struct SelectLaunch {
   int64_t idx_cap;
   void* scratch;         // 16-byte aligned, or NULL
   size_t scratch_bytes;  // below select_scratch_bytes(): one workgroup per row is used instead
-  uint32_t* counters = nullptr;      // arrival counters of the rows (zero between calls), or NULL
   const SelectPlan* plan = nullptr;  // NULL: select_plan() decides
 };
 tb_status launch_select(const SelectLaunch& a, hipStream_t st);
+// stage B alone, over kept keys that are already in the scratch (layout as above)
+tb_status launch_stage_b(const SelectLaunch& a, const SelectPlan& plan, hipStream_t st);
 
 struct AttnLaunch {
   const tb_cache_desc* desc;

@@ -1,14 +1,14 @@
 // Top-k selection under the policy "candidates = [lo, hi); keep the kk largest scores, lowest
 // index wins ties; emit ascending".
 //
-// One 1024-thread workgroup per (b,h).  Wave w owns the contiguous span [w*span, (w+1)*span)
-// of the head's scores and keeps their order-preserving 32-bit keys in registers (up to 64
-// per thread = 65536 scores; longer rows are streamed again in every phase).  The exact
+// The selection of one row (b,h) by one workgroup of W waves: wave w owns the contiguous span
+// [w*span, (w+1)*span) of the row's scores and keeps their order-preserving 32-bit keys in
+// registers (up to 64 per thread; longer rows are streamed again in every phase).  The exact
 // threshold key T (the kk-th largest) and the number r of keys equal to T that are still
 // needed are found by an MSB-first radix descent over LDS histograms:
 //
-//   bracket   a 12-bit histogram of a strided SAMPLE of the keys (4 per thread) gives a range of
-//             top-12-bit bins [b_lo, b_hi] that contains T unless the sample is wildly
+//   bracket   a 12-bit histogram of a strided SAMPLE of the keys (one per thread) gives a range
+//             of top-12-bit bins [b_lo, b_hi] that contains T unless the sample is wildly
 //             unrepresentative (the rank of T in the sample, +- 6 standard deviations);
 //   level 1   exact: every key above the bracket is counted, every key inside it goes into a
 //             histogram of up to 4096 sub-bins; if the exact counts show that T is NOT inside
@@ -17,25 +17,28 @@
 //   level 2+  the remaining low bits, 12 at a time, over the few keys of the chosen sub-bin.
 //
 // Output: {key > T} U {first r keys == T by index} in ascending order.  Positions come from
-// prefix sums (DPP scans inside a 256-key wave tile, running totals along the wave's span, 16
+// prefix sums (DPP scans inside a 256-key wave tile, running totals along the wave's span, the
 // wave totals across the workgroup) -- no atomic slot grabbing, so the result is ordered and
-// reproducible.  No global scratch is used.
+// reproducible.
 //
-// Long rows take two launches (prefilter_kernel, stage_b_kernel; see there): pieces of the row
-// keep the keys at or above a threshold sampled from the whole row, and the selection above runs
-// on what they kept.
+// Launch forms:
+//   select_kernel                      one 1024-thread workgroup per row, no global scratch;
+//   prefilter_kernel + stage_b_kernel  long rows: the row is cut into pieces, one workgroup per
+//                                      piece keeps the keys at or above the lower end of a bracket
+//                                      that every piece derives from the same sample of the row,
+//                                      and a second kernel selects among the kept keys.
+// stage_b_kernel also finishes a selection whose first stage ran inside the scoring kernel
+// (tb_score.hip), which leaves its kept keys in the same layout.
 #include "tb_device.h"
 #include "tb_internal.h"
 
 namespace tb {
 namespace {
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kWaveTile = kWave * 4;              // scores per wave tile: one float4 per lane
-constexpr int kTileElts = kSelWaves * kWaveTile;  // scores per workgroup-wide tile (4096)
-constexpr int kHistBins = 4096;                   // LDS histogram size (12 bits per level)
-constexpr int kTopShift = 20;                     // key >> 20 = top 12 bits
+constexpr int kWaveTile = kWave * 4;  // scores per wave tile: one float4 per lane
+constexpr int kHistBins = 4096;       // LDS histogram size (12 bits per level)
+constexpr int kTopShift = 20;         // key >> 20 = top 12 bits
+constexpr int kMaxPieces = 256;       // pieces of a row (the table of the second stage)
 
 struct SelectArgs {
   const float* scores;
@@ -45,28 +48,22 @@ struct SelectArgs {
   int32_t* idx;
   int32_t* count;
   int64_t idx_cap;
-  int32_t tiles_per_wave;
-  // Two-stage selection of long rows.  Stage A (prefilter_kernel) cuts the row into `pieces`
-  // pieces and keeps, per piece, the candidates whose key is not below a threshold that a
-  // sample of the whole row puts safely under the kk-th largest key: positions (of the whole
-  // row) and scores go to cand_idx / cand_score [unit][piece][cap] in position order, the
-  // number found to piece_count[unit][piece] (it may exceed cap: then the piece overflowed).
-  // Stage B (stage_b_kernel) selects the kk largest among the kept ones, read as one row
-  // through the table of piece counts; if the pieces hold fewer than kk keys together or one
-  // overflowed -- the sample misled -- it selects on the original row instead.
+  int32_t tiles_per_wave;  // of a workgroup that takes the whole row
+  // Selection by pieces.  Stage A cuts the row into `pieces` pieces and keeps, per piece, the
+  // candidates whose key is not below a threshold that a sample of the whole row puts safely
+  // under the kk-th largest key: positions (of the whole row) and keys go to cand_idx /
+  // cand_key [unit][piece][cap] in position order, and the piece's header {number found,
+  // b_lo, b_hi, 0} to piece_hdr[unit][piece].  Stage B selects the kk largest among the kept
+  // ones, read as one row through the table of the pieces' counts; if the pieces hold fewer
+  // than kk keys together or more than stage B has registers for -- the sample misled -- it
+  // selects on the original row instead.
   int32_t pieces;
   int64_t piece_len;
   int64_t cap;
   int32_t* cand_idx;
-  float* cand_score;
-  int32_t* piece_count;
-  uint32_t* arrive;  // one-launch form: the rows' arrival counters (kCounterStrideWords apart, zero between calls)
+  uint32_t* cand_key;
+  uint32_t* piece_hdr;
 };
-
-// A score whose key is `key` (the inverse of score_key up to the folding of NaN and -0).
-__device__ inline float key_to_score(uint32_t key) {
-  return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
-}
 
 // The four scores at positions n0 .. n0+3 (n0 a multiple of 4) as one 128-bit load without any
 // branch, so that a thread's loads can all be in flight together.  A row's allocation covers
@@ -75,21 +72,6 @@ __device__ inline float key_to_score(uint32_t key) {
 // keys_of4 -- which gets the unclamped position -- masks what was read.
 __device__ inline float4 load_scores4(const float* s, int64_t last4, int64_t n0) {
   return *reinterpret_cast<const float4*>(s + (n0 < last4 ? n0 : last4));
-}
-
-// Four consecutive floats (16-byte aligned) that another workgroup of the same launch has
-// written with agent-scope stores: read with agent-scope loads (two 64-bit ones), which are
-// served from the memory side of the per-XCD L2 caches and never from a stale line.
-__device__ inline float4 load_f4_agent(const float* p) {
-  const uint64_t* q = reinterpret_cast<const uint64_t*>(p);
-  const uint64_t x = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const uint64_t y = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  float4 f;
-  f.x = __uint_as_float(static_cast<uint32_t>(x));
-  f.y = __uint_as_float(static_cast<uint32_t>(x >> 32));
-  f.z = __uint_as_float(static_cast<uint32_t>(y));
-  f.w = __uint_as_float(static_cast<uint32_t>(y >> 32));
-  return f;
 }
 
 // Keys of the positions n0 .. n0+3.  Positions outside the candidate range [lo, hi) get key 0
@@ -108,19 +90,21 @@ __device__ inline void keys_of4(const float4& f, int lo, int hi, int64_t n0, uin
   }
 }
 
-// The 16 per-wave values in s_w (complete after a barrier): returns the sum of the entries of
-// the waves before this one and, in `total`, the sum of all.  Every wave scans the 16 values in
-// one DPP row (lane i of each row holds entry i) instead of adding up 16 LDS reads per thread.
+// The W per-wave values in s_w (complete after a barrier): returns the sum of the entries of
+// the waves before this one and, in `total`, the sum of all.  Every wave scans the values in
+// one DPP row (lane i < W of each row holds entry i) instead of adding up W LDS reads per thread.
+template <int W>
 __device__ inline uint32_t wave_entries_scan(const uint32_t* s_w, uint32_t& total) {
-  static_assert(kSelWaves == 16, "one DPP row holds the per-wave entries");
+  static_assert(W <= 16, "one DPP row holds the per-wave entries");
   constexpr int kRowShr = 0x110;
-  const uint32_t v = s_w[threadIdx.x & (kSelWaves - 1)];
+  const int l16 = threadIdx.x & 15;
+  const uint32_t v = l16 < W ? s_w[l16] : 0u;
   uint32_t incl = v;
   incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 1, 0xF, 0xF, false);
   incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 2, 0xF, 0xF, false);
-  incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 4, 0xF, 0xF, false);
-  incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 8, 0xF, 0xF, false);
-  total = __builtin_amdgcn_readlane(incl, kSelWaves - 1);
+  if (W > 4) incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 4, 0xF, 0xF, false);
+  if (W > 8) incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 8, 0xF, 0xF, false);
+  total = __builtin_amdgcn_readlane(incl, W - 1);
   return __builtin_amdgcn_readlane(incl - v, threadIdx.x / kWave);
 }
 
@@ -143,129 +127,165 @@ constexpr int kFoundWords = sizeof(Found) / 4;
 // leaves the preset {0, 0}.  The targets may depend on a second block-wide sum: every wave
 // reduces `extra`, and `targets(extra_total, need_a, need_b)` turns the total into the targets.
 //
-// The walk itself is done by wave 0 alone (the other 15 waves would only repeat it: on one
-// compute unit a workgroup-wide instruction costs 16 issue slots): lane l sums the 64 bins
-// [64*(63-l), 64*(63-l)+63] with 128-bit reads in a rotated order (conflict-free), a wave scan
-// finds the lane whose chunk contains the target, and the 64 lanes then scan that chunk.
-// Two barriers: the first completes the histogram that the callers fill with LDS atomics.
-// s_extra (16 words) and s_found (preset to 0) are per call site.
-template <typename Targets>
-__device__ inline Found find_bins(const uint32_t* s_hist, uint32_t extra, uint32_t* s_extra, Found* s_found,
-                                  Targets&& targets) {
+// All W waves take part: wave w owns the 4096/W bins below 4096 - (4096/W) w, lane l a run of
+// BL = 64/W adjacent bins (128-bit reads), so that (wave, lane, slot) ascending is bin
+// descending.  A DPP scan gives the running count inside the wave, the wave totals go through
+// LDS and are scanned by every wave; the one lane whose bins contain a target resolves it and
+// publishes the result.  Three barriers: the first completes the histogram that the callers
+// fill with LDS atomics.  s_extra (W words) is per call site, s_wsum (W words) may be shared by
+// all call sites, s_found is per call site and preset to 0.
+template <int W, typename Targets>
+__device__ inline Found find_bins(const uint32_t* s_hist, uint32_t extra, uint32_t* s_extra, uint32_t* s_wsum,
+                                  Found* s_found, Targets&& targets) {
+  constexpr int BW = kHistBins / W;  // bins per wave
+  constexpr int BL = BW / kWave;     // bins per lane
+  static_assert(BL >= 4 && BL % 4 == 0, "whole 128-bit reads per lane");
   const int lane = lane_id();
   const int wave = threadIdx.x / kWave;
   const uint32_t extra_incl = wave_incl_scan_u32(extra);
   if (lane == kWave - 1) s_extra[wave] = extra_incl;
   __syncthreads();  // the histogram and s_extra are complete
-  if (wave == 0) {
-    const int chunk = (kWave - 1 - lane) * 64;
-    uint32_t sum = 0;
+  const uint32_t bin0 = static_cast<uint32_t>(kHistBins - BW * (wave + 1) + BL * (kWave - 1 - lane));
+  uint32_t c[BL];  // ascending bins bin0 .. bin0 + BL - 1
+  uint32_t lsum = 0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const uint4 q = *reinterpret_cast<const uint4*>(s_hist + chunk + ((i + lane) & 15) * 4);
-      sum += (q.x + q.y) + (q.z + q.w);
-    }
-    const uint32_t incl = wave_incl_scan_u32(sum);
-    const uint32_t before = incl - sum;
-    uint32_t extra_total;
-    wave_entries_scan(s_extra, extra_total);
-    uint32_t need[2];
-    targets(extra_total, need[0], need[1]);
+  for (int i = 0; i < BL / 4; ++i) {
+    const uint4 q = *reinterpret_cast<const uint4*>(s_hist + bin0 + 4 * i);
+    c[4 * i] = q.x;
+    c[4 * i + 1] = q.y;
+    c[4 * i + 2] = q.z;
+    c[4 * i + 3] = q.w;
+    lsum += (q.x + q.y) + (q.z + q.w);
+  }
+  const uint32_t incl = wave_incl_scan_u32(lsum);
+  if (lane == kWave - 1) s_wsum[wave] = incl;
+  __syncthreads();
+  uint32_t total, extra_total;
+  const uint32_t before = wave_entries_scan<W>(s_wsum, total) + incl - lsum;  // count in bins above this lane's
+  wave_entries_scan<W>(s_extra, extra_total);
+  uint32_t need[2];
+  targets(extra_total, need[0], need[1]);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const unsigned long long hit = __ballot(before < need[t] && need[t] <= incl);
-      if (hit) {  // at most one lane: the chunk that contains the target
-        const int L = __ffsll(hit) - 1;
-        const uint32_t base = __builtin_amdgcn_readlane(before, L);
-        const uint32_t bin = static_cast<uint32_t>((kWave - 1 - L) * 64 + (kWave - 1 - lane));
-        const uint32_t v = s_hist[bin];
-        const uint32_t run = base + wave_incl_scan_u32(v) - v;
-        if (run < need[t] && need[t] <= run + v) {
-          if (t == 0) {
-            s_found->bin_a = bin;
-            s_found->above_a = run;
-            s_found->count_a = v;
-          } else {
-            s_found->bin_b = bin;
-            s_found->above_b = run;
-          }
+  for (int t = 0; t < 2; ++t) {
+    if (before < need[t] && need[t] <= before + lsum) {  // at most one thread of the workgroup
+      uint32_t run = before, bin = bin0 + BL - 1, cnt = c[BL - 1];
+#pragma unroll
+      for (int i = BL - 2; i >= 0; --i) {
+        if (need[t] > run + cnt) {  // not in this bin: go one down
+          run += cnt;
+          cnt = c[i];
+          --bin;
         }
       }
+      if (t == 0) {
+        s_found->bin_a = bin;
+        s_found->above_a = run;
+        s_found->count_a = cnt;
+      } else {
+        s_found->bin_b = bin;
+        s_found->above_b = run;
+      }
     }
-    if (lane == 0) {
-      s_found->extra_total = extra_total;
-      s_found->total = __builtin_amdgcn_readlane(incl, kWave - 1);
-      s_found->need_a = need[0];
-      s_found->need_b = need[1];
-    }
+  }
+  if (threadIdx.x == 0) {
+    s_found->extra_total = extra_total;
+    s_found->total = total;
+    s_found->need_a = need[0];
+    s_found->need_b = need[1];
   }
   __syncthreads();
   return *s_found;
 }
 
-// Streamed rows (NT == 0) keep the keys that fall inside the bracket in LDS, so that only two
-// passes read the scores: the bracketed level and the final write-out.
+// The bracket of top-12-bit bins that a sample of n_s keys (histogram s_hist) gives for the
+// kk-th largest of n_cand candidates: the rank of the threshold inside the sample and its
+// spread (binomial), in fp32 -- a heuristic only: exact counts decide afterwards whether the
+// bracket holds.
+template <int W>
+__device__ inline void sample_bracket(const uint32_t* s_hist, uint32_t n_valid, uint32_t* s_extra, uint32_t* s_wsum,
+                                      Found* s_found, int kk, int64_t n_cand, uint32_t& b_lo, uint32_t& b_hi) {
+  const Found fb = find_bins<W>(s_hist, n_valid, s_extra, s_wsum, s_found, [&](uint32_t n_s, uint32_t& na, uint32_t& nb) {
+    const float frac = static_cast<float>(kk) / static_cast<float>(n_cand);
+    const float ks_f = frac * static_cast<float>(n_s);
+    const float margin = 6.0f * sqrtf(ks_f * (1.0f - frac)) + 4.0f;
+    const float hi_f = ks_f - margin, lo_f = ks_f + margin;
+    na = hi_f < 1.0f ? 0u : static_cast<uint32_t>(hi_f);  // 0: no bin is safely above T
+    nb = lo_f >= static_cast<float>(n_s) ? n_s + 1u : static_cast<uint32_t>(lo_f) + 1u;
+  });
+  b_hi = fb.need_a ? fb.bin_a : (kHistBins - 1);         // top bin of the bracket
+  b_lo = (fb.need_b <= fb.extra_total) ? fb.bin_b : 1u;  // bottom bin of the bracket
+  if (b_lo < 1u) b_lo = 1u;                              // bin 0 holds only "not a candidate"
+  if (b_hi < b_lo) b_hi = b_lo;
+}
+
+// Streamed rows (NT == 0) may keep the keys that fall inside the bracket in LDS, so that only
+// two passes read the scores: the bracketed level and the final write-out.
 constexpr int kListCap = 16384;
 constexpr int kStreamBatch = 8;  // tiles in flight per wave while streaming
-
-constexpr int kMaxLevels = 4;  // bracketed level (possibly repeated once over all bins) + up to 2 levels of low bits
-
-constexpr int kMaxPieces = 16;
-constexpr int kOneLaunchStageBTiles = 8;  // one-launch form: stage B holds up to 32768 kept keys in registers
+constexpr int kMaxLevels = 4;    // bracketed level (possibly repeated once over all bins) + up to 2 levels of low bits
 
 // LDS of one selection (shared by the bodies that run one after the other in a kernel).
+template <int W>
 struct SelLds {
   uint32_t hist[2][kHistBins];  // alternating: one in use, the other being cleared
   __attribute__((aligned(16))) Found found[kMaxLevels + 1];
-  uint32_t part[2][kSelWaves];
-  uint32_t wgt[kSelWaves], weq[kSelWaves];
-  uint32_t wabove[kSelWaves];  // streamed rows: every wave's count of keys above the bracket
-  uint32_t nlist;              // streamed rows: keys appended to the list (unusable when beyond its capacity)
+  uint32_t part[2][W];
+  uint32_t wsum[W];
+  uint32_t wgt[W], weq[W];
+  uint32_t wabove[W];  // streamed rows: every wave's count of keys above the bracket
+  uint32_t nlist;      // streamed rows: keys appended to the list (unusable when beyond its capacity)
 };
 // Streamed rows that keep a list: keys inside the bracket (with the wave whose span they come
 // from) and per-(counting wave, owning wave) tallies of kept / tied keys.
+template <int W>
 struct ListLds {
   uint32_t ckey[kListCap];
   uint8_t cwave[kListCap];
-  uint32_t lcnt[kSelWaves][kSelWaves][2];
+  uint32_t lcnt[W][W][2];
+};
+// Stage B: where the pieces' kept keys lie in the row that stage B selects on.
+struct PieceTab {
+  uint32_t start[kMaxPieces];  // position of piece c's first kept key in that row (pieces padded to multiples of 4)
+  uint32_t n[kMaxPieces];      // kept keys of piece c
+  uint32_t len;                // length of the row
+  uint32_t b_lo, b_hi;         // the bracket the pieces agreed on
+  uint32_t ok;                 // the row of kept keys can be selected on
 };
 
-// STAGE 0: the selection of a row of scores; 2: stage B of a two-stage selection (the row is
-// what the pieces of stage A kept: `n_rows` keys read through the piece table in LDS); 3: the
-// same when the pieces ran in this very launch (their stores are read with agent-scope loads).
-// NT > 0: the wave's tiles are cached in registers (NT >= tiles per wave); NT == 0: the row is
-// streamed again in every phase; with a list (ll != nullptr) the keys inside the bracket are
-// kept in LDS and only two passes read the scores.
+// STAGE 0: the selection of a row of scores; 2: stage B of a selection by pieces (the row is
+// what the pieces kept, read through the piece table).
+// W: waves of the workgroup.  NT > 0: the wave's tiles are cached in registers (NT >= tiles per
+// wave); NT == 0: the row is streamed again in every phase; with LIST the keys inside the
+// bracket are kept in LDS and only two passes read the scores.
 // u: the row (b*Hq + h) this workgroup selects for.
-template <int NT, int STAGE, bool LIST = (NT == 0)>
-__device__ __forceinline__ void select_body(const SelectArgs& a, const int u, const uint32_t* s_ptab, SelLds& sl,
-                                            ListLds* ll) {
+template <int W, int NT, int STAGE, bool LIST>
+__device__ __forceinline__ void select_body(const SelectArgs& a, const int u, const PieceTab* tab, SelLds<W>& sl,
+                                            ListLds<W>* ll) {
   static_assert(!LIST || NT == 0, "only streamed rows keep a list");
+  constexpr int kThreads = W * kWave;
+  constexpr int kTileElts = W * kWaveTile;  // scores per workgroup-wide tile
   constexpr bool kStream = LIST;
-  constexpr bool kStageB = STAGE >= 2;   // the row is what the pieces kept
-  constexpr bool kAgent = STAGE == 3;    // ... written by other workgroups of this launch: agent-scope loads
+  constexpr bool kStageB = STAGE == 2;
   uint32_t (&s_hist)[2][kHistBins] = sl.hist;
   Found (&s_found)[kMaxLevels + 1] = sl.found;
-  uint32_t (&s_part)[2][kSelWaves] = sl.part;
-  uint32_t (&s_wgt)[kSelWaves] = sl.wgt;
-  uint32_t (&s_weq)[kSelWaves] = sl.weq;
-  uint32_t (&s_wabove)[kSelWaves] = sl.wabove;
+  uint32_t (&s_part)[2][W] = sl.part;
+  uint32_t (&s_wgt)[W] = sl.wgt;
+  uint32_t (&s_weq)[W] = sl.weq;
+  uint32_t (&s_wabove)[W] = sl.wabove;
   uint32_t& s_nlist = sl.nlist;
   uint32_t* s_ckey = kStream ? ll->ckey : nullptr;
   uint8_t* s_cwave = kStream ? ll->cwave : nullptr;
-  uint32_t (*s_lcnt)[kSelWaves][2] = kStream ? ll->lcnt : nullptr;
+  uint32_t (*s_lcnt)[W][2] = kStream ? ll->lcnt : nullptr;
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = tid / kWave;
   const int kk = a.kk;
   // stage B: the row is the concatenation of the pieces' kept keys, every piece padded to a
-  // multiple of 4 (s_ptab[c] = where piece c starts in it, s_ptab[kMaxPieces] = its length,
-  // s_ptab[kMaxPieces + 1 + c] = keys in piece c); every key of it is a candidate
-  const int64_t N = kStageB ? static_cast<int64_t>(s_ptab[kMaxPieces]) : a.N;
+  // multiple of 4; every key of it is a candidate
+  const int64_t N = kStageB ? static_cast<int64_t>(tab->len) : a.N;
   const int lo = kStageB ? 0 : a.lo, hi = kStageB ? static_cast<int>(N) : a.hi;
-  const float* s = kStageB ? a.cand_score + static_cast<int64_t>(u) * a.pieces * a.cap
-                              : a.scores + static_cast<int64_t>(u) * a.score_stride;
+  const float* s = a.scores + static_cast<int64_t>(u) * a.score_stride;
   int32_t* out = a.idx + static_cast<int64_t>(u) * a.idx_cap;
   // stage B: as many tiles per wave as the row needs (its length is not known at launch)
   const int tpw_b = static_cast<int>((N + kTileElts - 1) / kTileElts);
@@ -273,36 +293,46 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
   const int64_t wbase = static_cast<int64_t>(wave) * tpw * kWaveTile + lane * 4;
   const bool refine = kk > 0 && kk < hi - lo;
   const int64_t last4 = N > 0 ? ((N - 1) & ~int64_t{3}) : 0;  // the vector that holds the last score
-  // stage B: where position n (a multiple of 4) of the row lies in the [piece][cap] arrays, and
-  // how many of the four keys from there on are real (the rest is padding)
-  auto locate = [&](int64_t n, int& valid) -> int64_t {
-    int c = 0;
-#pragma unroll
-    for (int cc = 1; cc < kMaxPieces; ++cc) c += (cc < a.pieces && static_cast<int64_t>(s_ptab[cc]) <= n) ? 1 : 0;
-    const int64_t off = n - s_ptab[c];
-    valid = static_cast<int>(s_ptab[kMaxPieces + 1 + c]) - static_cast<int>(off);
-    return c * a.cap + off;
-  };
   uint32_t keys[NT > 0 ? NT : 1][4];
+  int32_t cidx[(kStageB && NT > 0) ? NT : 1][4];  // stage B: positions in the original row
   if (NT > 0 && kk > 0) {
-    float4 raw[NT > 0 ? NT : 1];  // every load of the thread is issued before the first is used
     if constexpr (kStageB) {
-      int valid[NT > 0 ? NT : 1];
+      // where position n (a multiple of 4) of the row lies in the [piece][cap] arrays, and how
+      // many of the four keys from there on are real (the rest is padding)
+      const uint32_t* ckeys = a.cand_key + static_cast<int64_t>(u) * a.pieces * a.cap;
+      const int32_t* cpos = a.cand_idx + static_cast<int64_t>(u) * a.pieces * a.cap;
+      uint4 rk[NT], ri[NT];
+      int valid[NT];
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int64_t n0 = wbase + j * kWaveTile;
         valid[j] = 0;
-        const int64_t phys = (j < tpw && n0 < N) ? locate(n0, valid[j]) : 0;
-        raw[j] = kAgent ? load_f4_agent(s + phys) : *reinterpret_cast<const float4*>(s + phys);
+        int64_t phys = 0;
+        if (j < tpw && n0 < N) {
+          int c = 0;  // the last piece that starts at or before n0 (binary search over the starts)
+#pragma unroll
+          for (int step = kMaxPieces / 2; step >= 1; step >>= 1)
+            if (c + step < a.pieces && static_cast<int64_t>(tab->start[c + step]) <= n0) c += step;
+          const int64_t off = n0 - tab->start[c];
+          valid[j] = static_cast<int>(tab->n[c]) - static_cast<int>(off);
+          phys = c * a.cap + off;
+        }
+        rk[j] = *reinterpret_cast<const uint4*>(ckeys + phys);
+        ri[j] = *reinterpret_cast<const uint4*>(cpos + phys);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        const float v[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
+        const uint32_t kv[4] = {rk[j].x, rk[j].y, rk[j].z, rk[j].w};
+        const uint32_t iv[4] = {ri[j].x, ri[j].y, ri[j].z, ri[j].w};
 #pragma unroll
-        for (int c = 0; c < 4; ++c) keys[j][c] = c < valid[j] ? score_key(v[c]) : 0u;
+        for (int c = 0; c < 4; ++c) {
+          keys[j][c] = c < valid[j] ? kv[c] : 0u;
+          cidx[(kStageB && NT > 0) ? j : 0][c] = static_cast<int32_t>(iv[c]);
+        }
       }
     } else {
+      float4 raw[NT > 0 ? NT : 1];  // every load of the thread is issued before the first is used
 #pragma unroll
       for (int j = 0; j < NT; ++j) raw[j] = load_scores4(s, last4, wbase + j * kWaveTile);
       __builtin_amdgcn_sched_barrier(0);
@@ -310,18 +340,23 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
       for (int j = 0; j < NT; ++j) keys_of4(raw[j], lo, hi, wbase + j * kWaveTile, keys[j]);
     }
   }
-  for (int i = tid; i < 2 * kHistBins; i += kSelThreads) (&s_hist[0][0])[i] = 0;
-  if (tid < (kMaxLevels + 1) * kFoundWords) reinterpret_cast<uint32_t*>(&s_found[0])[tid] = 0;
+  for (int i = tid; i < 2 * kHistBins; i += kThreads) (&s_hist[0][0])[i] = 0;
+  for (int i = tid; i < (kMaxLevels + 1) * kFoundWords; i += kThreads) reinterpret_cast<uint32_t*>(&s_found[0])[i] = 0;
   if (tid == 0) s_nlist = 0;
 
-  // always-kept ranges: sink prefix [0, lo) and local window [hi, N) of the original row
-  // (in stage B these are the ranges of the original row: a.lo, a.hi, a.N)
-  for (int64_t n = tid; n < a.lo; n += kSelThreads) out[n] = static_cast<int32_t>(n);
-  for (int64_t n = a.hi + tid; n < a.N; n += kSelThreads) out[a.lo + kk + (n - a.hi)] = static_cast<int32_t>(n);
-  if (tid == 0) a.count[u] = static_cast<int32_t>(a.lo + kk + (a.N - a.hi));
+  // always-kept ranges: sink prefix [0, lo) and local window [hi, N) of the original row (in
+  // stage B these are the ranges of the original row: a.lo, a.hi, a.N).  Written last: a global
+  // store that is still on its way would hold up the first barrier of the selection.
+  auto write_fixed_ranges = [&]() {
+    for (int64_t n = tid; n < a.lo; n += kThreads) out[n] = static_cast<int32_t>(n);
+    for (int64_t n = a.hi + tid; n < a.N; n += kThreads) out[a.lo + kk + (n - a.hi)] = static_cast<int32_t>(n);
+    if (tid == 0) a.count[u] = static_cast<int32_t>(a.lo + kk + (a.N - a.hi));
+  };
   int32_t* sel_out = out + a.lo;
-  const int32_t* remap = kStageB ? a.cand_idx + static_cast<int64_t>(u) * a.pieces * a.cap : nullptr;
-  if (kk == 0) return;
+  if (kk == 0) {
+    write_fixed_ranges();
+    return;
+  }
 
   // visit every tile of this wave's span: body(j, keys of the tile)
   auto for_each_tile = [&](auto&& body) {
@@ -355,44 +390,35 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
   bool list_ok = false;  // streamed rows: the LDS list holds every key inside the bracket
   if (refine) {
     __syncthreads();  // LDS initialised
-    // ---- bracket from a sample: the first key of (up to) four tiles per thread
-    constexpr int kSamples = (NT > 0 && NT < 4) ? NT : 4;
-    uint32_t n_valid = 0;
-    float4 sraw[kSamples];
-    if constexpr (NT == 0) {
-#pragma unroll
-      for (int i = 0; i < kSamples; ++i)
-        sraw[i] = load_scores4(s, last4, wbase + static_cast<int64_t>((i * tpw) / kSamples) * kWaveTile);
-    }
-#pragma unroll
-    for (int i = 0; i < kSamples; ++i) {
+    uint32_t b_lo, b_hi;
+    if constexpr (kStageB) {
+      // the pieces have already derived the bracket from their sample of the row
+      b_lo = tab->b_lo;
+      b_hi = tab->b_hi;
+    } else {
+      // ---- bracket from a sample: one key per thread, the first key of a tile that varies with
+      // the lane so that the sample is spread over the wave's span.  (More keys would narrow the
+      // bracket a little, but they land in a handful of exponent bins and their LDS atomics
+      // serialise.)
+      uint32_t n_valid = 0;
+      const int st = lane % tpw;  // tile sampled by this lane
       uint32_t ks;
       if constexpr (NT > 0) {
-        ks = keys[kStageB ? i : (i * NT) / kSamples][0];  // (stage B: the row may end after a few tiles)
+        ks = keys[0][0];
+#pragma unroll
+        for (int j = 1; j < NT; ++j) ks = (j == st) ? keys[j][0] : ks;
       } else {
+        const int64_t n0 = wbase + static_cast<int64_t>(st) * kWaveTile;
         uint32_t k4[4];
-        keys_of4(sraw[i], lo, hi, wbase + static_cast<int64_t>((i * tpw) / kSamples) * kWaveTile, k4);
+        keys_of4(load_scores4(s, last4, n0), lo, hi, n0, k4);
         ks = k4[0];
       }
       if (ks) {
         atomicAdd(&s_hist[0][ks >> kTopShift], 1u);
-        ++n_valid;
+        n_valid = 1;
       }
+      sample_bracket<W>(s_hist[0], n_valid, s_part[0], sl.wsum, &s_found[0], kk, hi - lo, b_lo, b_hi);
     }
-    // rank of the threshold inside the sample and its spread (binomial), in fp32: a heuristic
-    // only -- the exact counts of level 1 decide whether the bracket holds
-    const Found fb = find_bins(s_hist[0], n_valid, s_part[0], &s_found[0], [&](uint32_t n_s, uint32_t& na, uint32_t& nb) {
-      const float frac = static_cast<float>(kk) / static_cast<float>(hi - lo);
-      const float ks_f = frac * static_cast<float>(n_s);
-      const float margin = 6.0f * sqrtf(ks_f * (1.0f - frac)) + 4.0f;
-      const float hi_f = ks_f - margin, lo_f = ks_f + margin;
-      na = hi_f < 1.0f ? 0u : static_cast<uint32_t>(hi_f);  // 0: no bin is safely above T
-      nb = lo_f >= static_cast<float>(n_s) ? n_s + 1u : static_cast<uint32_t>(lo_f) + 1u;
-    });
-    uint32_t b_hi = fb.need_a ? fb.bin_a : (kHistBins - 1);            // top bin of the bracket
-    uint32_t b_lo = (fb.need_b <= fb.extra_total) ? fb.bin_b : 1u;     // bottom bin of the bracket
-    if (b_lo < 1u) b_lo = 1u;                                   // bin 0 holds only "not a candidate"
-    if (b_hi < b_lo) b_hi = b_lo;
 
     // ---- radix descent.  Level state: candidates are the keys with lo_key <= key < lo_key +
     // span, histogrammed by (key - lo_key) >> shift; keys above `above_key` (only on the
@@ -461,7 +487,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
       } else if (kStream && list_ok) {
         // streamed row: the keys of the chosen sub-bin are all in the LDS list
         const uint32_t nl = s_nlist;
-        for (uint32_t i = tid; i < nl; i += kSelThreads) {
+        for (uint32_t i = tid; i < nl; i += kThreads) {
           const uint32_t d = s_ckey[kStream ? i : 0] - lo_key;
           if (d < span) atomicAdd(&h[d >> shift], 1u);
         }
@@ -479,15 +505,16 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
         });
       }
       // clear the other histogram for the next level while this one is being filled
-      for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[cur ^ 1][i] = 0;
-      const Found f = find_bins(h, n_above, s_part[call & 1], &s_found[call], [&](uint32_t c_above, uint32_t& na, uint32_t& nb) {
-        na = (c_above < need) ? need - c_above : 0u;
-        nb = 0u;
-      });
+      for (int i = tid; i < kHistBins; i += kThreads) s_hist[cur ^ 1][i] = 0;
+      const Found f = find_bins<W>(h, n_above, s_part[call & 1], sl.wsum, &s_found[call],
+                                   [&](uint32_t c_above, uint32_t& na, uint32_t& nb) {
+                                     na = (c_above < need) ? need - c_above : 0u;
+                                     nb = 0u;
+                                   });
       const uint32_t want = f.need_a, total_in = f.total;
       if (kStream && call == 1) {
         list_ok = s_nlist <= static_cast<uint32_t>(kListCap);
-        if (tid < kSelWaves) s_wabove[tid] = s_part[1][tid];  // per-wave counts of keys above the bracket
+        if (tid < W) s_wabove[tid] = s_part[1][tid];  // per-wave counts of keys above the bracket
       }
       cur ^= 1;
       if (want >= 1u && want <= total_in) {  // T lies inside this level's range: descend
@@ -536,10 +563,10 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
   if (kStream && list_ok) {
     // streamed row: the per-wave totals come from the list instead of another pass over the
     // scores (a key above the bracket is kept for sure; a key below it never is)
-    for (int i = tid; i < (kStream ? kSelWaves : 1) * kSelWaves * 2; i += kSelThreads) (&s_lcnt[0][0][0])[i] = 0;
+    for (int i = tid; i < (kStream ? W : 1) * W * 2; i += kThreads) (&s_lcnt[0][0][0])[i] = 0;
     __syncthreads();
     const uint32_t nl = s_nlist;
-    for (uint32_t i = tid; i < nl; i += kSelThreads) {
+    for (uint32_t i = tid; i < nl; i += kThreads) {
       const uint32_t key = s_ckey[kStream ? i : 0];
       const uint32_t w = s_cwave[kStream ? i : 0];
       if (key > T) {
@@ -549,9 +576,9 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
       }
     }
     __syncthreads();
-    if (tid < kSelWaves) {
+    if (tid < W) {
       uint32_t gt = s_wabove[tid], eq = 0;
-      for (int cw = 0; cw < (kStream ? kSelWaves : 1); ++cw) {
+      for (int cw = 0; cw < (kStream ? W : 1); ++cw) {
         gt += s_lcnt[cw][tid][0];
         eq += s_lcnt[cw][tid][1];
       }
@@ -576,19 +603,10 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
   __syncthreads();
   // kept / tied keys in the spans of the waves before this one
   uint32_t unused_total;
-  uint32_t base_gt = wave_entries_scan(s_wgt, unused_total);
-  uint32_t base_eq = wave_entries_scan(s_weq, unused_total);
+  uint32_t base_gt = wave_entries_scan<W>(s_wgt, unused_total);
+  uint32_t base_eq = wave_entries_scan<W>(s_weq, unused_total);
 
   // Pass B: position of a kept key = (#greater before it) + min(#equal before it, r_eq)
-  int64_t tile_phys = 0;  // stage B: where the current tile's four keys lie in the [piece][cap] arrays
-  auto emit = [&](uint32_t pos, int32_t n, int c) {
-    if (pos < static_cast<uint32_t>(kk)) {
-      if constexpr (STAGE == 0) sel_out[pos] = n + c;
-      if constexpr (kStageB)  // position in the original row
-        sel_out[pos] = kAgent ? __hip_atomic_load(&remap[tile_phys + c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                              : remap[tile_phys + c];
-    }
-  };
   for_each_tile([&](int j, const uint32_t(&k4)[4]) {
     const uint32_t cnt = tile_count(k4);
     uint32_t excl;
@@ -601,17 +619,16 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
     uint32_t gt_before = base_gt + (excl & 0xFFFFu);
     uint32_t eq_before = base_eq + (excl >> 16);
     const int32_t nn = static_cast<int32_t>(wbase + static_cast<int64_t>(j) * kWaveTile);
-    if constexpr (kStageB) {
-      int valid;
-      tile_phys = nn < N ? locate(nn, valid) : 0;
-    }
+    auto emit = [&](uint32_t pos, int c) {
+      if (pos < static_cast<uint32_t>(kk)) sel_out[pos] = kStageB ? cidx[(kStageB && NT > 0) ? j : 0][c] : nn + c;
+    };
     if ((tot >> 16) == 0) {
       // no key of this wave tile equals T: the tie count is the same for every slot
       uint32_t pos = gt_before + (eq_before < r_eq ? eq_before : r_eq);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         if (k4[c] > T) {
-          emit(pos, nn, c);
+          emit(pos, c);
           ++pos;
         }
       }
@@ -620,9 +637,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
       for (int c = 0; c < 4; ++c) {
         const bool gt = k4[c] > T;
         const bool eq = (k4[c] == T) && T;
-        if (gt || (eq && eq_before < r_eq)) {
-          emit(gt_before + (eq_before < r_eq ? eq_before : r_eq), nn, c);
-        }
+        if (gt || (eq && eq_before < r_eq)) emit(gt_before + (eq_before < r_eq ? eq_before : r_eq), c);
         gt_before += gt ? 1u : 0u;
         eq_before += eq ? 1u : 0u;
       }
@@ -630,31 +645,31 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
     base_gt += tot & 0xFFFFu;
     base_eq += tot >> 16;
   });
+  write_fixed_ranges();
 }
+
+constexpr int kSelWaves = 16;  // one workgroup per row
+constexpr int kSelThreads = kSelWaves * kWave;
 
 template <int NT>
 __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void select_kernel(SelectArgs a) {
-  __shared__ SelLds sl;
+  __shared__ SelLds<kSelWaves> sl;
   if constexpr (NT == 0) {
-    __shared__ ListLds ll;
-    select_body<0, 0>(a, blockIdx.x, nullptr, sl, &ll);
+    __shared__ ListLds<kSelWaves> ll;
+    select_body<kSelWaves, 0, 0, true>(a, blockIdx.x, nullptr, sl, &ll);
   } else {
-    select_body<NT, 0>(a, blockIdx.x, nullptr, sl, nullptr);
+    select_body<kSelWaves, NT, 0, false>(a, blockIdx.x, nullptr, sl, nullptr);
   }
 }
 
-// ---- selection of a row by several workgroups, stage A.  One workgroup per (row, piece); the
-// piece's keys stay in registers (NT tiles per wave, piece_len <= 65536).  Every piece of a row
-// takes the same sample of the row's candidates (4096 positions spread over [lo, hi)) and so
-// arrives at the same threshold: the lower end of the bracket that the one-workgroup selection
-// would use.  AGENT: the kept keys are read by another workgroup of the same launch, so they
-// are written with agent-scope stores (through the L2 of this XCD).
-template <int NT, bool AGENT>
-__device__ __forceinline__ void prefilter_body(const SelectArgs& a, const int u, const int c, SelLds& sl) {
+// ---- selection of a row by pieces, stage A.  The piece's keys are in registers (NT tiles per
+// wave).  Every piece of a row takes the same sample of the row's candidates (one 128-bit load
+// per thread at positions spread evenly over [lo, hi)) and so arrives at the same bracket as its
+// siblings.  The keys at or above the bracket's lower end are kept, in position order.
+template <int W, int NT>
+__device__ __forceinline__ void piece_body(const SelectArgs& a, const int u, const int c, SelLds<W>& sl) {
+  constexpr int kThreads = W * kWave;
   uint32_t* s_hist = sl.hist[0];
-  Found& s_found = sl.found[0];
-  uint32_t* s_part = sl.part[0];
-  uint32_t* s_wcnt = sl.wgt;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = tid / kWave;
@@ -668,12 +683,10 @@ __device__ __forceinline__ void prefilter_body(const SelectArgs& a, const int u,
   const float* s = row + base;
   const int64_t last4 = n_c > 0 ? ((n_c - 1) & ~int64_t{3}) : 0;
   const int64_t wbase = static_cast<int64_t>(wave) * NT * kWaveTile + lane * 4;
-  // the sample of the whole row: 256 clusters of 16 adjacent scores (one 64-byte line each, so
-  // that sampling does not pull the whole row through the caches once more), spread evenly over
-  // the candidates; four threads share a cluster with one 128-bit load each
+  // the sample of the whole row: the first of four adjacent scores at each of `kThreads` positions
+  // spread evenly over the candidates
   const int64_t span = a.hi - a.lo;
-  int64_t sp = a.lo + ((tid / 4) * span) / (kSelThreads / 4);
-  sp = (sp & ~int64_t{15}) + (tid % 4) * 4;
+  const int64_t sp = (a.lo + (tid * span) / kThreads) & ~int64_t{3};
   const int64_t row_last4 = (a.N - 1) & ~int64_t{3};
   uint32_t keys[NT][4];
   float4 sraw;
@@ -688,32 +701,21 @@ __device__ __forceinline__ void prefilter_body(const SelectArgs& a, const int u,
       keys_of4(raw[j], static_cast<int>(lo_c), static_cast<int>(hi_c), wbase + j * kWaveTile, keys[j]);
   }
 
-  for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
-  if (tid < kFoundWords) reinterpret_cast<uint32_t*>(&s_found)[tid] = 0;
+  for (int i = tid; i < kHistBins; i += kThreads) s_hist[i] = 0;
+  if (tid < kFoundWords) reinterpret_cast<uint32_t*>(&sl.found[0])[tid] = 0;
   __syncthreads();
   uint32_t n_valid = 0;
   {
     uint32_t sk[4];
-    keys_of4(sraw, a.lo, a.hi, sp, sk);  // (a cluster may straddle an end of the candidate range)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (sk[i]) {
-        atomicAdd(&s_hist[sk[i] >> kTopShift], 1u);
-        ++n_valid;
-      }
+    keys_of4(sraw, a.lo, a.hi, sp, sk);  // (the four may straddle an end of the candidate range)
+    uint32_t ks = sk[0] ? sk[0] : (sk[1] ? sk[1] : (sk[2] ? sk[2] : sk[3]));
+    if (ks) {
+      atomicAdd(&s_hist[ks >> kTopShift], 1u);
+      n_valid = 1;
     }
   }
-  const int kk = a.kk;
-  const Found fb = find_bins(s_hist, n_valid, s_part, &s_found, [&](uint32_t n_s, uint32_t& na, uint32_t& nb) {
-    const float frac = static_cast<float>(kk) / static_cast<float>(span);
-    const float ks_f = frac * static_cast<float>(n_s);
-    const float margin = 6.0f * sqrtf(ks_f * (1.0f - frac)) + 4.0f;
-    const float lo_f = ks_f + margin;
-    na = 0u;
-    nb = lo_f >= static_cast<float>(n_s) ? n_s + 1u : static_cast<uint32_t>(lo_f) + 1u;
-  });
-  uint32_t b_lo = (fb.need_b <= fb.extra_total) ? fb.bin_b : 1u;
-  if (b_lo < 1u) b_lo = 1u;
+  uint32_t b_lo, b_hi;
+  sample_bracket<W>(s_hist, n_valid, sl.part[0], sl.wsum, &sl.found[0], a.kk, span, b_lo, b_hi);
   const uint32_t t_lo = b_lo << kTopShift;  // keys from here up are kept
 
   // ordered compaction of the piece's kept keys (prefix sums as in the selection itself)
@@ -728,18 +730,15 @@ __device__ __forceinline__ void prefilter_body(const SelectArgs& a, const int u,
     pre[j] = run + incl - cnt;
     run += __builtin_amdgcn_readlane(incl, kWave - 1);
   }
-  if (lane == 0) s_wcnt[wave] = run;
+  if (lane == 0) sl.wgt[wave] = run;
   __syncthreads();
   uint32_t total;
-  const uint32_t wave_base = wave_entries_scan(s_wcnt, total);
+  const uint32_t wave_base = wave_entries_scan<W>(sl.wgt, total);
   int32_t* out_idx = a.cand_idx + (static_cast<int64_t>(u) * a.pieces + c) * a.cap;
-  float* out_score = a.cand_score + (static_cast<int64_t>(u) * a.pieces + c) * a.cap;
-  int32_t* out_count = a.piece_count + static_cast<int64_t>(u) * a.pieces + c;
-  if (tid == 0) {
-    if (AGENT)
-      __hip_atomic_store(out_count, static_cast<int32_t>(total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else
-      *out_count = static_cast<int32_t>(total);
+  uint32_t* out_key = a.cand_key + (static_cast<int64_t>(u) * a.pieces + c) * a.cap;
+  if (tid < 3) {
+    uint32_t* hdr = a.piece_hdr + (static_cast<int64_t>(u) * a.pieces + c) * 4;
+    hdr[tid] = tid == 0 ? total : (tid == 1 ? b_lo : b_hi);
   }
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
@@ -748,15 +747,8 @@ __device__ __forceinline__ void prefilter_body(const SelectArgs& a, const int u,
     for (int e = 0; e < 4; ++e) {
       if (keys[j][e] >= t_lo) {
         if (pos < static_cast<uint32_t>(a.cap)) {
-          const int32_t n = static_cast<int32_t>(base + wbase + j * kWaveTile + e);
-          const float sc = key_to_score(keys[j][e]);  // same key again in stage B
-          if (AGENT) {
-            __hip_atomic_store(&out_idx[pos], n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&out_score[pos], sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          } else {
-            out_idx[pos] = n;
-            out_score[pos] = sc;
-          }
+          out_idx[pos] = static_cast<int32_t>(base + wbase + j * kWaveTile + e);
+          out_key[pos] = keys[j][e];
         }
         ++pos;
       }
@@ -765,100 +757,53 @@ __device__ __forceinline__ void prefilter_body(const SelectArgs& a, const int u,
 }
 
 // ---- stage B.  One workgroup per row: builds the table of the pieces' kept keys and selects
-// among them, or -- when the pieces kept fewer than kk keys, one of them overflowed, or they kept
-// more than this instance holds in registers -- selects on the original row (one streaming
+// among them, or -- when the pieces kept fewer than kk keys, one of them ran out of room, or they
+// kept more than this instance holds in registers -- selects on the original row (one streaming
 // workgroup: slow, but it only happens when the sample of stage A was wildly unrepresentative).
-// s_ptab: 2 * kMaxPieces + 3 words.
-template <int NT, bool AGENT>
-__device__ __forceinline__ void stage_b_body(const SelectArgs& a, const int u, SelLds& sl, ListLds* ll,
-                                             uint32_t* s_ptab) {
+template <int NT>
+__global__ __launch_bounds__(kSelThreads, 4) void stage_b_kernel(SelectArgs a) {
+  constexpr int W = kSelWaves;
+  __shared__ SelLds<W> sl;
+  __shared__ ListLds<W> ll;
+  __shared__ PieceTab tab;
+  __shared__ uint32_t s_scan[2][W + 1];
   const int tid = threadIdx.x;
-  if (tid < kWave) {  // wave 0: one lane per piece
-    const int32_t* cnt = a.piece_count + static_cast<int64_t>(u) * a.pieces;
-    uint32_t n = 0;
-    if (tid < a.pieces)
-      n = static_cast<uint32_t>(AGENT ? __hip_atomic_load(&cnt[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                      : cnt[tid]);
-    const uint32_t padded = (n + 3u) & ~3u;
-    const uint32_t incl_p = wave_incl_scan_u32(padded);
-    const uint32_t incl_n = wave_incl_scan_u32(n);
-    const unsigned long long over = __ballot(n > static_cast<uint32_t>(a.cap));
-    if (tid < kMaxPieces) {
-      s_ptab[tid] = incl_p - padded;
-      s_ptab[kMaxPieces + 1 + tid] = n;
-    }
-    if (tid == kWave - 1) {
-      s_ptab[kMaxPieces] = incl_p;  // length of the row of kept keys
-      const bool ok = !over && incl_p <= static_cast<uint32_t>(NT * kTileElts) && incl_n >= static_cast<uint32_t>(a.kk);
-      s_ptab[2 * kMaxPieces + 2] = ok ? 1u : 0u;
-    }
+  const int u = blockIdx.x;
+  const uint32_t* hdr = a.piece_hdr + static_cast<int64_t>(u) * a.pieces * 4;
+  uint32_t n = 0;
+  if (tid < a.pieces) n = hdr[tid * 4];
+  const uint32_t padded = (n + 3u) & ~3u;
+  uint32_t len, kept;
+  const uint32_t start = block_excl_scan<W>(padded, s_scan[0], len);
+  block_excl_scan<W>(n, s_scan[1], kept);
+  const int over = __syncthreads_or(n > static_cast<uint32_t>(a.cap));
+  if (tid < kMaxPieces) {
+    tab.start[tid] = start;
+    tab.n[tid] = n;
+  }
+  if (tid == 0) {
+    tab.len = len;
+    tab.b_lo = hdr[1];
+    tab.b_hi = hdr[2];
+    tab.ok = (!over && len <= static_cast<uint32_t>(NT * W * kWaveTile) && kept >= static_cast<uint32_t>(a.kk)) ? 1u : 0u;
   }
   __syncthreads();
-  if (s_ptab[2 * kMaxPieces + 2]) {
-    select_body<NT, AGENT ? 3 : 2>(a, u, s_ptab, sl, nullptr);
-  } else if (ll) {
-    select_body<0, 0, true>(a, u, nullptr, sl, ll);
+  if (tab.ok) {
+    select_body<W, NT, 2, false>(a, u, &tab, sl, nullptr);
   } else {
-    select_body<0, 0, false>(a, u, nullptr, sl, nullptr);
+    select_body<W, 0, 0, true>(a, u, nullptr, sl, &ll);
   }
 }
 
 template <int NT>
 __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void prefilter_kernel(SelectArgs a) {
-  __shared__ SelLds sl;
-  prefilter_body<NT, false>(a, blockIdx.x / a.pieces, blockIdx.x % a.pieces, sl);
+  __shared__ SelLds<kSelWaves> sl;
+  piece_body<kSelWaves, NT>(a, blockIdx.x / a.pieces, blockIdx.x % a.pieces, sl);
 }
-
-template <int NT>
-__global__ __launch_bounds__(kSelThreads, 4) void stage_b_kernel(SelectArgs a) {
-  __shared__ SelLds sl;
-  __shared__ ListLds ll;
-  __shared__ uint32_t s_ptab[2 * kMaxPieces + 3];
-  stage_b_body<NT, false>(a, blockIdx.x, sl, &ll, s_ptab);
-}
-
-// ---- both stages in one launch.  The pieces of a row publish what they kept with agent-scope
-// stores, wait until those stores have been acknowledged, and take a ticket from the row's
-// arrival counter; the piece that draws the last ticket runs stage B for the row and puts the
-// counter back to zero.
-//
-// Why the last piece sees the others' data.  Agent-scope stores are written through the L2 of
-// the storing XCD to the memory side, where the L2s of all XCDs meet; a store counts against
-// the wave's vector-memory counter until that write is acknowledged, so after `s_waitcnt
-// vmcnt(0)` in every storing wave and the workgroup barrier, all stores of the workgroup have
-// reached the memory side.  Only then does thread 0 issue the ticket, a read-modify-write that
-// is itself performed at the memory side and hence ordered there after the stores of every
-// piece whose ticket precedes it.  The drawer of the last ticket issues its agent-scope loads
-// after the ticket has returned (they depend on it through the branch and a barrier); such
-// loads bypass the L2 lines of the reading XCD, so they return the acknowledged data.
-template <int NTA, int NTB>
-__global__ __launch_bounds__(kSelThreads, 4) void select_pieces_kernel(SelectArgs a) {
-  __shared__ SelLds sl;
-  __shared__ uint32_t s_ptab[2 * kMaxPieces + 3];
-  __shared__ uint32_t s_last;
-  const int u = blockIdx.x / a.pieces, c = blockIdx.x % a.pieces;
-  prefilter_body<NTA, true>(a, u, c, sl);
-  __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0): this wave's agent-scope stores have been acknowledged
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t* counter = a.arrive + static_cast<int64_t>(u) * kCounterStrideWords;
-    const uint32_t ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const bool last = ticket == static_cast<uint32_t>(a.pieces - 1);
-    if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
-    s_last = last ? 1u : 0u;
-  }
-  __syncthreads();
-  if (!s_last) return;
-  stage_b_body<NTB, true>(a, u, sl, nullptr, s_ptab);
-}
-
-}  // namespace
-
-namespace {
 
 tb_status launch_whole(const SelectArgs& a, int64_t units, hipStream_t st) {
   SelectArgs b = a;
-  const int32_t tiles = static_cast<int32_t>((a.N + kTileElts - 1) / kTileElts);  // per wave
+  const int32_t tiles = static_cast<int32_t>((a.N + kSelWaves * kWaveTile - 1) / (kSelWaves * kWaveTile));  // per wave
   b.tiles_per_wave = tiles;
   dim3 grid(static_cast<unsigned>(units));
   dim3 block(kSelThreads);
@@ -879,6 +824,38 @@ tb_status launch_whole(const SelectArgs& a, int64_t units, hipStream_t st) {
 
 }  // namespace
 
+// Second stage over kept keys that are already in place (layout of SelectArgs::cand_*).
+tb_status launch_stage_b(const SelectLaunch& L, const SelectPlan& plan, hipStream_t st) {
+  SelectArgs a;
+  a.scores = L.scores;
+  a.score_stride = L.score_stride;
+  a.N = L.N;
+  a.kk = L.kk;
+  a.lo = L.lo;
+  a.hi = L.hi;
+  a.idx = L.idx;
+  a.count = L.count;
+  a.idx_cap = L.idx_cap;
+  const int64_t per_unit = static_cast<int64_t>(plan.pieces) * plan.cap;
+  a.pieces = plan.pieces;
+  a.piece_len = plan.piece_len;
+  a.cap = plan.cap;
+  a.cand_idx = static_cast<int32_t*>(L.scratch);
+  a.cand_key = reinterpret_cast<uint32_t*>(a.cand_idx + L.units * per_unit);
+  a.piece_hdr = a.cand_key + L.units * per_unit;
+  a.tiles_per_wave = static_cast<int32_t>((L.N + kSelWaves * kWaveTile - 1) / (kSelWaves * kWaveTile));  // fall-back on the whole row
+  const dim3 grid(static_cast<unsigned>(L.units)), block(kSelThreads);
+  if (plan.stage_b_tiles <= 2)
+    hipLaunchKernelGGL(stage_b_kernel<2>, grid, block, 0, st, a);
+  else if (plan.stage_b_tiles <= 4)
+    hipLaunchKernelGGL(stage_b_kernel<4>, grid, block, 0, st, a);
+  else if (plan.stage_b_tiles <= 8)
+    hipLaunchKernelGGL(stage_b_kernel<8>, grid, block, 0, st, a);
+  else  // (more than 65536 kept keys falls back to the whole row inside the kernel)
+    hipLaunchKernelGGL(stage_b_kernel<16>, grid, block, 0, st, a);
+  return hip_status(hipGetLastError());
+}
+
 tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   if (L.units == 0) return TB_OK;
   SelectArgs a;
@@ -896,65 +873,34 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   a.piece_len = 0;
   a.cap = 0;
   a.cand_idx = nullptr;
-  a.cand_score = nullptr;
-  a.piece_count = nullptr;
-  a.arrive = L.counters;
+  a.cand_key = nullptr;
+  a.piece_hdr = nullptr;
   const SelectPlan plan = L.plan ? *L.plan : select_plan(L.units, L.hi - L.lo, L.N, L.kk);
   if (plan.pieces <= 1 || !L.scratch || L.scratch_bytes < select_scratch_bytes(L.units, plan))
     return launch_whole(a, L.units, st);
 
-  // scratch: kept positions, kept scores ([units][pieces][cap] each), then the pieces' counts
+  // scratch: kept positions, kept keys ([units][pieces][cap] each), then the pieces' headers
   const int64_t per_unit = static_cast<int64_t>(plan.pieces) * plan.cap;
   a.pieces = plan.pieces;
   a.piece_len = plan.piece_len;
   a.cap = plan.cap;
   a.cand_idx = static_cast<int32_t*>(L.scratch);
-  a.cand_score = reinterpret_cast<float*>(a.cand_idx + L.units * per_unit);
-  a.piece_count = reinterpret_cast<int32_t*>(a.cand_score + L.units * per_unit);
-  a.tiles_per_wave = static_cast<int32_t>((L.N + kTileElts - 1) / kTileElts);  // for the fall-back on the whole row
-  dim3 block(kSelThreads);
-  const dim3 grid_a(static_cast<unsigned>(L.units * plan.pieces));
-  const int tiles_a = static_cast<int>((plan.piece_len + kTileElts - 1) / kTileElts);
-  if (plan.one_launch && L.counters) {
-    constexpr int NTB = kOneLaunchStageBTiles;
-    if (tiles_a <= 1)
-      hipLaunchKernelGGL((select_pieces_kernel<1, NTB>), grid_a, block, 0, st, a);
-    else if (tiles_a <= 2)
-      hipLaunchKernelGGL((select_pieces_kernel<2, NTB>), grid_a, block, 0, st, a);
-    else if (tiles_a <= 4)
-      hipLaunchKernelGGL((select_pieces_kernel<4, NTB>), grid_a, block, 0, st, a);
-    else if (tiles_a <= 8)
-      hipLaunchKernelGGL((select_pieces_kernel<8, NTB>), grid_a, block, 0, st, a);
-    else
-      hipLaunchKernelGGL((select_pieces_kernel<16, NTB>), grid_a, block, 0, st, a);
-    return hip_status(hipGetLastError());
-  }
-  {
-    if (tiles_a <= 1)
-      hipLaunchKernelGGL(prefilter_kernel<1>, grid_a, block, 0, st, a);
-    else if (tiles_a <= 2)
-      hipLaunchKernelGGL(prefilter_kernel<2>, grid_a, block, 0, st, a);
-    else if (tiles_a <= 4)
-      hipLaunchKernelGGL(prefilter_kernel<4>, grid_a, block, 0, st, a);
-    else if (tiles_a <= 8)
-      hipLaunchKernelGGL(prefilter_kernel<8>, grid_a, block, 0, st, a);
-    else
-      hipLaunchKernelGGL(prefilter_kernel<16>, grid_a, block, 0, st, a);
-    if (hipGetLastError() != hipSuccess) return TB_ERR_HIP;
-  }
-  {
-    dim3 grid(static_cast<unsigned>(L.units));
-    const int tiles = static_cast<int>((per_unit + kTileElts - 1) / kTileElts);  // at most: the pieces' capacity
-    if (tiles <= 2)
-      hipLaunchKernelGGL(stage_b_kernel<2>, grid, block, 0, st, a);
-    else if (tiles <= 4)
-      hipLaunchKernelGGL(stage_b_kernel<4>, grid, block, 0, st, a);
-    else if (tiles <= 8)
-      hipLaunchKernelGGL(stage_b_kernel<8>, grid, block, 0, st, a);
-    else  // (more than 65536 kept keys falls back to the whole row inside the kernel)
-      hipLaunchKernelGGL(stage_b_kernel<16>, grid, block, 0, st, a);
-  }
-  return hip_status(hipGetLastError());
+  a.cand_key = reinterpret_cast<uint32_t*>(a.cand_idx + L.units * per_unit);
+  a.piece_hdr = a.cand_key + L.units * per_unit;
+  const dim3 grid(static_cast<unsigned>(L.units * plan.pieces)), block(kSelThreads);
+  const int tiles = static_cast<int>((plan.piece_len + kSelWaves * kWaveTile - 1) / (kSelWaves * kWaveTile));
+  if (tiles <= 1)
+    hipLaunchKernelGGL(prefilter_kernel<1>, grid, block, 0, st, a);
+  else if (tiles <= 2)
+    hipLaunchKernelGGL(prefilter_kernel<2>, grid, block, 0, st, a);
+  else if (tiles <= 4)
+    hipLaunchKernelGGL(prefilter_kernel<4>, grid, block, 0, st, a);
+  else if (tiles <= 8)
+    hipLaunchKernelGGL(prefilter_kernel<8>, grid, block, 0, st, a);
+  else
+    hipLaunchKernelGGL(prefilter_kernel<16>, grid, block, 0, st, a);
+  if (hipGetLastError() != hipSuccess) return TB_ERR_HIP;
+  return launch_stage_b(L, plan, st);
 }
 
 }  // namespace tb
