@@ -351,7 +351,6 @@ tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* 
   if (!ws || !aligned16(ws) || ws_bytes < w.total) return TB_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   ScoreLaunch S{d, q_imp, Kimp, score_scale, scores, score_stride};
-  TB_TRY(launch_score(S, st));
 
   SelectLaunch L;
   L.units = units;
@@ -366,6 +365,7 @@ tb_status tb_decode_step(const tb_cache_desc* d, const void* q_imp, const void* 
   L.idx_cap = idx_cap;
   L.scratch = static_cast<char*>(ws) + w.part_off;
   L.scratch_bytes = ws_bytes - w.part_off;
+  TB_TRY(launch_score(S, st));
   TB_TRY(launch_select(L, st));
 
   AttnLaunch A{d,   q,   K,   V,

@@ -50,8 +50,7 @@ tb_status launch_score(const ScoreLaunch& a, hipStream_t st);
 // is cut into `pieces` pieces, every piece keeps the candidates that a sample of the row puts
 // at or above the k-th largest (stage A, one workgroup per piece), and the final kk are
 // selected among the kept ones (stage B, a second kernel).  pieces == 1: one workgroup per row,
-// no scratch.  The same plan describes the kept keys that the scoring kernel leaves behind when
-// it runs stage A itself (one piece per tile of rows it scores).
+// no scratch.
 struct SelectPlan {
   int pieces;
   int64_t piece_len;  // scores per piece
@@ -78,8 +77,6 @@ struct SelectLaunch {
   const SelectPlan* plan = nullptr;  // NULL: select_plan() decides
 };
 tb_status launch_select(const SelectLaunch& a, hipStream_t st);
-// stage B alone, over kept keys that are already in the scratch (layout as above)
-tb_status launch_stage_b(const SelectLaunch& a, const SelectPlan& plan, hipStream_t st);
 
 struct AttnLaunch {
   const tb_cache_desc* desc;

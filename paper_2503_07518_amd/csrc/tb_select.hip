@@ -27,8 +27,6 @@
 //                                      piece keeps the keys at or above the lower end of a bracket
 //                                      that every piece derives from the same sample of the row,
 //                                      and a second kernel selects among the kept keys.
-// stage_b_kernel also finishes a selection whose first stage ran inside the scoring kernel
-// (tb_score.hip), which leaves its kept keys in the same layout.
 #include "tb_device.h"
 #include "tb_internal.h"
 
@@ -234,6 +232,8 @@ struct SelLds {
   uint32_t wgt[W], weq[W];
   uint32_t wabove[W];  // streamed rows: every wave's count of keys above the bracket
   uint32_t nlist;      // streamed rows: keys appended to the list (unusable when beyond its capacity)
+  uint32_t ntiny;      // keys gathered from a sparsely populated sub-bin
+  uint32_t tiny[kWave];
 };
 // Streamed rows that keep a list: keys inside the bracket (with the wave whose span they come
 // from) and per-(counting wave, owning wave) tallies of kept / tied keys.
@@ -342,7 +342,10 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
   }
   for (int i = tid; i < 2 * kHistBins; i += kThreads) (&s_hist[0][0])[i] = 0;
   for (int i = tid; i < (kMaxLevels + 1) * kFoundWords; i += kThreads) reinterpret_cast<uint32_t*>(&s_found[0])[i] = 0;
-  if (tid == 0) s_nlist = 0;
+  if (tid == 0) {
+    s_nlist = 0;
+    sl.ntiny = 0;
+  }
 
   // always-kept ranges: sink prefix [0, lo) and local window [hi, N) of the original row (in
   // stage B these are the ranges of the original row: a.lo, a.hi, a.N).  Written last: a global
@@ -520,10 +523,41 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
       if (want >= 1u && want <= total_in) {  // T lies inside this level's range: descend
         lo_key += f.bin_a << shift;
         need = want - f.above_a;
-        if (shift == 0) break;
         if (need == f.count_a) {
           // every key of this sub-bin is needed: no reason to look at its low bits
           take_whole_bin = true;
+          break;
+        }
+        if (shift == 0) break;
+        if (NT > 0 && f.count_a <= static_cast<uint32_t>(kWave)) {
+          // A handful of keys share the sub-bin (the usual case after the bracketed level: its
+          // sub-bins are a few thousand key values wide): instead of another histogram level,
+          // gather them -- one lane each -- and rank them against each other in every wave.
+          const uint32_t sub = 1u << shift;
+          for_each_tile([&](int, const uint32_t(&k4)[4]) {
+            const uint32_t d0 = k4[0] - lo_key, d1 = k4[1] - lo_key, d2 = k4[2] - lo_key, d3 = k4[3] - lo_key;
+            const uint32_t dmin = min(min(d0, d1), min(d2, d3));
+            if (__any(dmin < sub)) {
+#pragma unroll
+              for (int c = 0; c < 4; ++c)
+                if (k4[c] - lo_key < sub) sl.tiny[atomicAdd(&sl.ntiny, 1u)] = k4[c];
+            }
+          });
+          __syncthreads();
+          const int n_tiny = static_cast<int>(f.count_a);
+          const uint32_t mine = lane < n_tiny ? sl.tiny[lane] : 0u;
+          uint32_t greater = 0, equal = 0;
+          for (int j = 0; j < n_tiny; ++j) {
+            const uint32_t other = __builtin_amdgcn_readlane(mine, j);
+            greater += other > mine ? 1u : 0u;
+            equal += other == mine ? 1u : 0u;
+          }
+          // the key whose ranks (greater, greater + equal] contain `need` is the threshold
+          const unsigned long long hit = __ballot(lane < n_tiny && greater < need && need <= greater + equal);
+          const int L = __ffsll(hit) - 1;  // (several lanes when the threshold value repeats: they agree)
+          lo_key = static_cast<uint32_t>(__builtin_amdgcn_readlane(mine, L));
+          need -= static_cast<uint32_t>(__builtin_amdgcn_readlane(greater, L));
+          if (need == static_cast<uint32_t>(__builtin_amdgcn_readlane(equal, L))) take_whole_bin = true;  // every key equal to it is kept
           break;
         }
         const int nshift = shift > 12 ? shift - 12 : 0;
@@ -551,100 +585,111 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
   // kk == hi - lo: T = 0 keeps every candidate (all real keys are > 0)
 
   // ---- ordered compaction.  Pass A: prefix of {key > T} (low half) and {key == T} (high
-  // half) inside each wave tile, and the wave's totals.
-  auto tile_count = [&](const uint32_t(&k4)[4]) {
-    uint32_t cnt = 0;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) cnt += (k4[c] > T ? 1u : 0u) + ((k4[c] == T && T) ? 0x10000u : 0u);
-    return cnt;
-  };
-  constexpr bool kKeepPre = NT > 0 && NT <= 8;  // keep the in-tile prefixes when registers allow
-  uint32_t pre[kKeepPre ? NT : 1];
-  if (kStream && list_ok) {
-    // streamed row: the per-wave totals come from the list instead of another pass over the
-    // scores (a key above the bracket is kept for sure; a key below it never is)
-    for (int i = tid; i < (kStream ? W : 1) * W * 2; i += kThreads) (&s_lcnt[0][0][0])[i] = 0;
-    __syncthreads();
-    const uint32_t nl = s_nlist;
-    for (uint32_t i = tid; i < nl; i += kThreads) {
-      const uint32_t key = s_ckey[kStream ? i : 0];
-      const uint32_t w = s_cwave[kStream ? i : 0];
-      if (key > T) {
-        atomicAdd(&s_lcnt[kStream ? wave : 0][w][0], 1u);
-      } else if (key == T) {
-        atomicAdd(&s_lcnt[kStream ? wave : 0][w][1], 1u);
-      }
-    }
-    __syncthreads();
-    if (tid < W) {
-      uint32_t gt = s_wabove[tid], eq = 0;
-      for (int cw = 0; cw < (kStream ? W : 1); ++cw) {
-        gt += s_lcnt[cw][tid][0];
-        eq += s_lcnt[cw][tid][1];
-      }
-      s_wgt[tid] = gt;
-      s_weq[tid] = eq;
-    }
-  } else {
-    uint32_t run_gt = 0, run_eq = 0;
-    for_each_tile([&](int j, const uint32_t(&k4)[4]) {
-      const uint32_t cnt = tile_count(k4);
-      const uint32_t incl = wave_incl_scan_u32(cnt);
-      if (kKeepPre) pre[kKeepPre ? j : 0] = incl - cnt;
-      const uint32_t tot = __builtin_amdgcn_readlane(incl, kWave - 1);
-      run_gt += tot & 0xFFFFu;
-      run_eq += tot >> 16;
-    });
-    if (lane == 0) {
-      s_wgt[wave] = run_gt;
-      s_weq[wave] = run_eq;
-    }
-  }
-  __syncthreads();
-  // kept / tied keys in the spans of the waves before this one
-  uint32_t unused_total;
-  uint32_t base_gt = wave_entries_scan<W>(s_wgt, unused_total);
-  uint32_t base_eq = wave_entries_scan<W>(s_weq, unused_total);
-
-  // Pass B: position of a kept key = (#greater before it) + min(#equal before it, r_eq)
-  for_each_tile([&](int j, const uint32_t(&k4)[4]) {
-    const uint32_t cnt = tile_count(k4);
-    uint32_t excl;
-    if (kKeepPre) {
-      excl = pre[kKeepPre ? j : 0];
-    } else {
-      excl = wave_incl_scan_u32(cnt) - cnt;
-    }
-    const uint32_t tot = __builtin_amdgcn_readlane(excl + cnt, kWave - 1);
-    uint32_t gt_before = base_gt + (excl & 0xFFFFu);
-    uint32_t eq_before = base_eq + (excl >> 16);
-    const int32_t nn = static_cast<int32_t>(wbase + static_cast<int64_t>(j) * kWaveTile);
-    auto emit = [&](uint32_t pos, int c) {
-      if (pos < static_cast<uint32_t>(kk)) sel_out[pos] = kStageB ? cidx[(kStageB && NT > 0) ? j : 0][c] : nn + c;
-    };
-    if ((tot >> 16) == 0) {
-      // no key of this wave tile equals T: the tie count is the same for every slot
-      uint32_t pos = gt_before + (eq_before < r_eq ? eq_before : r_eq);
+  // half) inside each wave tile, and the wave's totals.  TIES == false: no key equal to T has
+  // to be cut (r_eq == 0: every kept key is > T), so the equal-to-T bookkeeping is left out.
+  auto compact = [&](auto ties_tag) {
+    constexpr bool TIES = decltype(ties_tag)::value;
+    auto tile_count = [&](const uint32_t(&k4)[4]) {
+      uint32_t cnt = 0;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        if (k4[c] > T) {
-          emit(pos, c);
-          ++pos;
+        cnt += k4[c] > T ? 1u : 0u;
+        if (TIES) cnt += (k4[c] == T) ? 0x10000u : 0u;
+      }
+      return cnt;
+    };
+    constexpr bool kKeepPre = NT > 0 && NT <= 8;  // keep the in-tile prefixes when registers allow
+    uint32_t pre[kKeepPre ? NT : 1];
+    if (kStream && list_ok) {
+      // streamed row: the per-wave totals come from the list instead of another pass over the
+      // scores (a key above the bracket is kept for sure; a key below it never is)
+      for (int i = tid; i < (kStream ? W : 1) * W * 2; i += kThreads) (&s_lcnt[0][0][0])[i] = 0;
+      __syncthreads();
+      const uint32_t nl = s_nlist;
+      for (uint32_t i = tid; i < nl; i += kThreads) {
+        const uint32_t key = s_ckey[kStream ? i : 0];
+        const uint32_t w = s_cwave[kStream ? i : 0];
+        if (key > T) {
+          atomicAdd(&s_lcnt[kStream ? wave : 0][w][0], 1u);
+        } else if (key == T) {
+          atomicAdd(&s_lcnt[kStream ? wave : 0][w][1], 1u);
         }
       }
+      __syncthreads();
+      if (tid < W) {
+        uint32_t gt = s_wabove[tid], eq = 0;
+        for (int cw = 0; cw < (kStream ? W : 1); ++cw) {
+          gt += s_lcnt[cw][tid][0];
+          eq += s_lcnt[cw][tid][1];
+        }
+        s_wgt[tid] = gt;
+        s_weq[tid] = eq;
+      }
     } else {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bool gt = k4[c] > T;
-        const bool eq = (k4[c] == T) && T;
-        if (gt || (eq && eq_before < r_eq)) emit(gt_before + (eq_before < r_eq ? eq_before : r_eq), c);
-        gt_before += gt ? 1u : 0u;
-        eq_before += eq ? 1u : 0u;
+      uint32_t run_gt = 0, run_eq = 0;
+      for_each_tile([&](int j, const uint32_t(&k4)[4]) {
+        const uint32_t cnt = tile_count(k4);
+        const uint32_t incl = wave_incl_scan_u32(cnt);
+        if (kKeepPre) pre[kKeepPre ? j : 0] = incl - cnt;
+        const uint32_t tot = __builtin_amdgcn_readlane(incl, kWave - 1);
+        run_gt += tot & 0xFFFFu;
+        run_eq += tot >> 16;
+      });
+      if (lane == 0) {
+        s_wgt[wave] = run_gt;
+        s_weq[wave] = run_eq;
       }
     }
-    base_gt += tot & 0xFFFFu;
-    base_eq += tot >> 16;
-  });
+    __syncthreads();
+    // kept / tied keys in the spans of the waves before this one
+    uint32_t unused_total;
+    uint32_t base_gt = wave_entries_scan<W>(s_wgt, unused_total);
+    uint32_t base_eq = TIES ? wave_entries_scan<W>(s_weq, unused_total) : 0u;
+
+    // Pass B: position of a kept key = (#greater before it) + min(#equal before it, r_eq)
+    for_each_tile([&](int j, const uint32_t(&k4)[4]) {
+      const uint32_t cnt = tile_count(k4);
+      uint32_t excl;
+      if (kKeepPre) {
+        excl = pre[kKeepPre ? j : 0];
+      } else {
+        excl = wave_incl_scan_u32(cnt) - cnt;
+      }
+      const uint32_t tot = __builtin_amdgcn_readlane(excl + cnt, kWave - 1);
+      uint32_t gt_before = base_gt + (excl & 0xFFFFu);
+      uint32_t eq_before = base_eq + (excl >> 16);
+      const int32_t nn = static_cast<int32_t>(wbase + static_cast<int64_t>(j) * kWaveTile);
+      auto emit = [&](uint32_t pos, int c) {
+        if (pos < static_cast<uint32_t>(kk)) sel_out[pos] = kStageB ? cidx[(kStageB && NT > 0) ? j : 0][c] : nn + c;
+      };
+      if (!TIES || (tot >> 16) == 0) {
+        // no key of this wave tile equals T: the tie count is the same for every slot
+        uint32_t pos = gt_before + (TIES ? (eq_before < r_eq ? eq_before : r_eq) : 0u);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          if (k4[c] > T) {
+            emit(pos, c);
+            ++pos;
+          }
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const bool gt = k4[c] > T;
+          const bool eq = k4[c] == T;
+          if (gt || (eq && eq_before < r_eq)) emit(gt_before + (eq_before < r_eq ? eq_before : r_eq), c);
+          gt_before += gt ? 1u : 0u;
+          eq_before += eq ? 1u : 0u;
+        }
+      }
+      base_gt += tot & 0xFFFFu;
+      base_eq += tot >> 16;
+    });
+  };
+  if (r_eq != 0)
+    compact(std::true_type{});
+  else
+    compact(std::false_type{});
   write_fixed_ranges();
 }
 
@@ -822,9 +867,7 @@ tb_status launch_whole(const SelectArgs& a, int64_t units, hipStream_t st) {
   return hip_status(hipGetLastError());
 }
 
-}  // namespace
-
-// Second stage over kept keys that are already in place (layout of SelectArgs::cand_*).
+// Second stage over kept keys that are in place (layout of SelectArgs::cand_*).
 tb_status launch_stage_b(const SelectLaunch& L, const SelectPlan& plan, hipStream_t st) {
   SelectArgs a;
   a.scores = L.scores;
@@ -855,6 +898,8 @@ tb_status launch_stage_b(const SelectLaunch& L, const SelectPlan& plan, hipStrea
     hipLaunchKernelGGL(stage_b_kernel<16>, grid, block, 0, st, a);
   return hip_status(hipGetLastError());
 }
+
+}  // namespace
 
 tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   if (L.units == 0) return TB_OK;
