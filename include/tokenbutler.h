@@ -126,6 +126,20 @@ tb_status tb_sparse_decode_attn_shared(const tb_cache_desc* desc, const void* q,
                                        int64_t max_count, int64_t tail_begin, int64_t tail_end, float sm_scale,
                                        float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
 
+/* tb_sparse_decode_attn for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments minus ws / ws_bytes, same kernels and bit-identical results.  The scratch (arrival
+ * counters and split partials) lives in a device array inside the library, 4 MiB per GPU, held
+ * from the first call on that GPU until the process ends.  A shape whose scratch would exceed
+ * that (tb_workspace_bytes(TB_OP_ATTN, ...) > 4 MiB) is rejected with TB_ERR_WORKSPACE before
+ * anything is launched.  The call allocates nothing and enqueues a small fill kernel (the
+ * counters are cleared on every call) followed by the attention kernel.  All calls on one GPU
+ * share the array: calls that overlap in time on one GPU (different streams) race. */
+tb_status tb_sparse_decode_attn_static(const tb_cache_desc* desc, const void* q, const void* K, const void* V,
+                                       const int32_t* idx, const int32_t* count, int64_t idx_cap,
+                                       int64_t max_count, int64_t tail_begin, int64_t tail_end, float sm_scale,
+                                       float* out, float* lse, void* stream);
+
 /* Migration of selected rows into the "Important Buffer" (Sec. 3.3 "Inference Setup": the
  * paper keeps the attended tokens in contiguous buffers and copies the selection there on
  * prediction steps).  Kbuf/Vbuf[b,h,i,:] = K/V[b,h/g,idx[b,h,i],:] for i < min(count[b,h], max_count).

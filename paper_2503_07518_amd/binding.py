@@ -22,7 +22,7 @@ TB_OP_SELECT, TB_OP_ATTN, TB_OP_DECODE_STEP = 1, 2, 3
 
 EXPORTS = (
     "tb_project_keys", "tb_score", "tb_select_topk", "tb_expand_neighbors", "tb_sparse_decode_attn",
-    "tb_sparse_decode_attn_shared",
+    "tb_sparse_decode_attn_shared", "tb_sparse_decode_attn_static",
     "tb_gather_kv", "tb_buffered_decode_attn", "tb_predict_queries", "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_read_stream_probe", "tb_status_string", "tb_version",
 )
 
@@ -71,6 +71,7 @@ def load_library() -> ctypes.CDLL:
     L.tb_expand_neighbors.argtypes = [i32, i32, i64, i32, i32, vp, vp, i64, vp, vp, i64, vp]
     L.tb_sparse_decode_attn.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, i64, f32, vp, vp, vp, sz, vp]
     L.tb_sparse_decode_attn_shared.argtypes = L.tb_sparse_decode_attn.argtypes
+    L.tb_sparse_decode_attn_static.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, i64, f32, vp, vp, vp]
     L.tb_decode_step.argtypes = [dp, vp, vp, f32, vp, vp, vp, i32, i32, i32, f32, vp, i64, vp, vp, i64, vp, vp,
                                  vp, sz, vp]
     L.tb_gather_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, vp, vp, i64, vp]
@@ -235,6 +236,16 @@ def tb_sparse_decode_attn(desc, q, K, V, idx, count, max_count: int, sm_scale: f
                                                 sm_scale, _ptr(out), _ptr(lse), _ptr(ws),
                                                 ws.numel() * ws.element_size(), _stream(stream)),
            "tb_sparse_decode_attn")
+
+
+def tb_sparse_decode_attn_static(desc, q, K, V, idx, count, max_count: int, sm_scale: float, out, lse,
+                                 tail_begin: int = 0, tail_end: int = 0, stream=None) -> None:
+    """tb_sparse_decode_attn with the library's own scratch (no workspace, no allocation)."""
+    assert q.is_contiguous() and out.is_contiguous()
+    _check(load_library().tb_sparse_decode_attn_static(ctypes.byref(desc), _ptr(q), _ptr(K), _ptr(V), _ptr(idx),
+                                                       _ptr(count), idx.stride(-2), max_count, tail_begin,
+                                                       tail_end, sm_scale, _ptr(out), _ptr(lse), _stream(stream)),
+           "tb_sparse_decode_attn_static")
 
 
 def tb_sparse_decode_attn_shared(desc, q, K, V, idx, count, max_count: int, sm_scale: float, out, lse, ws,

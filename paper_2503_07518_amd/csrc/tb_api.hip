@@ -1,5 +1,7 @@
 // C ABI of libtokenbutler: argument validation on the host, workspace layout, launch plans.
 // Every entry point only enqueues kernels on the caller's stream.
+#include <mutex>
+
 #include "tb_internal.h"
 
 namespace tb {
@@ -78,6 +80,30 @@ WsLayout ws_layout(int64_t units, int D, int nsplit) {
 }
 
 namespace {
+
+// Scratch of tb_sparse_decode_attn_static: device memory that the library owns, one copy per
+// GPU, held from the first use on that GPU until the process ends.  Host code never passes the
+// array's name to a kernel (on the host it is only a stand-in for the symbol): the device
+// address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = size_t{4} << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+tb_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TB_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TB_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return TB_OK;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -274,6 +300,31 @@ tb_status tb_sparse_decode_attn_shared(const tb_cache_desc* d, const void* q, co
                                        float* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
   return sparse_attn(d, q, K, V, idx, count, idx_cap, max_count, tail_begin, tail_end, sm_scale, out, lse, ws,
                      ws_bytes, stream, true);
+}
+
+tb_status tb_sparse_decode_attn_static(const tb_cache_desc* d, const void* q, const void* K, const void* V,
+                                       const int32_t* idx, const int32_t* count, int64_t idx_cap,
+                                       int64_t max_count, int64_t tail_begin, int64_t tail_end, float sm_scale,
+                                       float* out, float* lse, void* stream) {
+  TB_TRY(check_attn_args(d, q, K, V, idx, count, idx_cap, max_count, tail_begin, tail_end, out));
+  const int64_t units = static_cast<int64_t>(d->B) * d->Hq;
+  if (units == 0) return TB_OK;
+  const AttnPlan plan = attn_plan(units, max_count + (tail_end - tail_begin), attn_tile_rows_per_wg(d->dtype, d->D));
+  const WsLayout w = ws_layout(units, d->D, plan.nsplit);
+  if (w.total > kStaticScratchBytes) return TB_ERR_WORKSPACE;  // beyond the library's own scratch
+  void* ws = nullptr;
+  TB_TRY(static_scratch(&ws));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // the arrival counters must be zero when the kernel starts; the array keeps whatever the
+  // last call on this GPU left, so they are cleared here (a fill kernel, not a memset node:
+  // callers may be capturing a graph)
+  TB_TRY(launch_fill_zero(ws, w.part_off, st));
+  AttnLaunch L{d,   q,   K,   V,
+               idx, count, idx_cap, max_count, tail_begin, tail_end,
+               sm_scale, out, lse,
+               reinterpret_cast<float*>(static_cast<char*>(ws) + w.part_off),
+               reinterpret_cast<uint32_t*>(ws), plan};
+  return launch_attn(L, st);
 }
 
 tb_status tb_gather_kv(const tb_cache_desc* d, const void* K, const void* V, const int32_t* idx, const int32_t* count,
