@@ -309,29 +309,35 @@ class IntervalDriver:
         self.exp_idx = None
         self.exp_cnt = None
 
-    def step(self, t: int, N_t: int, q, q_imp, K, V, Kimp):
-        """K, V, Kimp hold at least N_t rows; only the first N_t are visible.  Returns
-        (out, lse, idx_used, count_used)."""
-        Kt = np.ascontiguousarray(K[:, :, :N_t])
-        Vt = np.ascontiguousarray(V[:, :, :N_t])
+    def lists(self, t: int, N_t: int, q_imp, Kimp):
+        """The token lists that step t attends over: (idx, count).  On a prediction step the
+        scores and the selection are made (and the widened selection is stored); on the other
+        steps the stored widened list is followed by the tokens appended since the prediction."""
         if t % self.P == 0:
             s = score(q_imp, np.ascontiguousarray(Kimp[:, :, :N_t]), self.dtype, self.scale)
             sel, cnt = select_topk(s, self.k, self.sink, self.window)
             self.N_pred = N_t
             self.exp_idx, self.exp_cnt = expand_neighbors(sel, cnt, N_t, self.radius, mode=self.mode)
-            use_idx, use_cnt = (self.exp_idx, self.exp_cnt) if self.expand_on_predict else (sel, cnt)
-        else:
-            extra = N_t - self.N_pred
-            B, Hq = self.exp_cnt.shape
-            cap = self.exp_idx.shape[-1] + extra
-            use_idx = np.full((B, Hq, cap), -1, dtype=np.int32)
-            use_cnt = self.exp_cnt + extra
-            tail = np.arange(self.N_pred, N_t, dtype=np.int32)
-            for b in range(B):
-                for h in range(Hq):
-                    c = int(self.exp_cnt[b, h])
-                    use_idx[b, h, :c] = self.exp_idx[b, h, :c]
-                    use_idx[b, h, c:c + extra] = tail
+            return (self.exp_idx, self.exp_cnt) if self.expand_on_predict else (sel, cnt)
+        extra = N_t - self.N_pred
+        B, Hq = self.exp_cnt.shape
+        cap = self.exp_idx.shape[-1] + extra
+        use_idx = np.full((B, Hq, cap), -1, dtype=np.int32)
+        use_cnt = self.exp_cnt + extra
+        tail = np.arange(self.N_pred, N_t, dtype=np.int32)
+        for b in range(B):
+            for h in range(Hq):
+                c = int(self.exp_cnt[b, h])
+                use_idx[b, h, :c] = self.exp_idx[b, h, :c]
+                use_idx[b, h, c:c + extra] = tail
+        return use_idx, use_cnt
+
+    def step(self, t: int, N_t: int, q, q_imp, K, V, Kimp):
+        """K, V, Kimp hold at least N_t rows; only the first N_t are visible.  Returns
+        (out, lse, idx_used, count_used)."""
+        use_idx, use_cnt = self.lists(t, N_t, q_imp, Kimp)
+        Kt = np.ascontiguousarray(K[:, :, :N_t])
+        Vt = np.ascontiguousarray(V[:, :, :N_t])
         if self.headless:
             out, lse = sparse_decode_attn_shared(q, Kt, Vt, use_idx[:, 0], use_cnt[:, 0], self.dtype, self.sm_scale)
         else:

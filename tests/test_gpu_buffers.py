@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import DEV, dtype_name, gpu_attn, np_of
+from gpu_util import DEV, assert_attention, dtype_name, gpu_attn, np_of
 from paper_2503_07518_amd import binding as tb, interval, workloads
 
 pytestmark = pytest.mark.gpu
@@ -71,8 +71,7 @@ def test_gather_kv_and_buffered_attention(oracle, dtype, B, Hq, Hkv, D, N, cap):
             full[b, h, :c] = np_of(idx)[b, h, :c]
             full[b, h, c:c + 7] = np.arange(tail[0], tail[1])
     ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K), np_of(V), full, cn + 7, dtype_name(K), sm)
-    tol = 1e-5 if dtype == torch.float32 else 2e-2
-    assert np.abs(np_of(out) - ro).max() <= tol and np.abs(np_of(lse) - rl).max() <= 1e-3
+    assert_attention(np_of(out), ro, dtype_name(K), np_of(lse), rl)
 
 
 def test_buffered_interval_matches_fused_interval(oracle):

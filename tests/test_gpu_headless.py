@@ -9,7 +9,8 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import DEV, dtype_name, gpu_attn, gpu_score, gpu_select, np_of
+from gpu_util import (DEV, assert_attention, assert_scores, dtype_name, gpu_attn, gpu_score, gpu_select, np_of,
+                      score_magnitude)
 from paper_2503_07518_amd import binding as tb
 
 pytestmark = pytest.mark.gpu
@@ -60,7 +61,7 @@ def test_headless_pipeline(oracle, dtype, B, Hq, Hkv, D, N, k, sink, window):
     idx, cnt = gpu_select(scores, N, k, sink, window)          # [B][1][cap], [B][1]
     torch.cuda.synchronize()
     r_scores = oracle.score(np_of(q_imp), np_of(Kimp), dtype_name(Kimp), 1.0)
-    assert np.allclose(np_of(scores)[..., :N], r_scores, rtol=1e-4, atol=1e-5)
+    assert_scores(np_of(scores)[..., :N], r_scores, score_magnitude(oracle, np_of(q_imp), np_of(Kimp), dtype_name(Kimp), 1))
     # the list is checked on the GPU's own scores, so that fp32 rounding decides nothing
     r_idx, r_cnt = oracle.select_topk(np_of(scores)[..., :N], k, sink, window)
     assert np.array_equal(np_of(cnt), r_cnt)
@@ -70,9 +71,7 @@ def test_headless_pipeline(oracle, dtype, B, Hq, Hkv, D, N, k, sink, window):
     out, lse = shared_attn(q, K, V, idx, cnt.reshape(B), N, sm, idx.shape[-1])
     r_out, r_lse = oracle.sparse_decode_attn_shared(np_of(q), np_of(K), np_of(V), r_idx.reshape(B, -1),
                                                     r_cnt.reshape(B), dtype_name(K), sm)
-    tol = 2e-2 if dtype == torch.bfloat16 else 1e-5
-    assert np.allclose(np_of(out), r_out, atol=tol, rtol=0)
-    assert np.allclose(np_of(lse), r_lse, atol=1e-3, rtol=1e-4)
+    assert_attention(np_of(out), r_out, dtype_name(K), np_of(lse), r_lse)
 
     # same rows in the same order through the per-head entry point
     rep_idx = idx.expand(B, Hq, idx.shape[-1]).contiguous()
@@ -105,8 +104,7 @@ def test_headless_tail_and_ragged_counts(oracle, B):
         r_idx[b, :eff[b]] = np_of(idx)[b, :eff[b]]
         r_idx[b, eff[b]:eff[b] + 7] = np.arange(tail[0], tail[1])
     r_out, r_lse = oracle.sparse_decode_attn_shared(np_of(q), np_of(K), np_of(V), r_idx, eff + 7, "bf16", 0.09)
-    assert np.allclose(np_of(out), r_out, atol=2e-2, rtol=0)
-    assert np.allclose(np_of(lse), r_lse, atol=1e-3, rtol=1e-4)
+    assert_attention(np_of(out), r_out, "bf16", np_of(lse), r_lse)
 
 
 @pytest.mark.parametrize("name", ["C2_llama3_8b_32k", "C3_batched_depth", "C5_long_context"])
@@ -132,14 +130,15 @@ def test_headless_full_size_configs(oracle, name):
     assert np.array_equal(np_of(cnt), r_cnt) and np.array_equal(np_of(idx), r_idx)
     out, lse = shared_attn(q, K, V, idx, cnt.reshape(B), N, cfg.sm_scale, idx.shape[-1])
     rng = np.random.default_rng(5)
-    for _ in range(4):
-        b, h = int(rng.integers(B)), int(rng.integers(Hq))
+    units = [(b, h) for b in range(B) for h in range(Hq)]
+    if len(units) > 64:
+        units = [units[i] for i in rng.choice(len(units), 64, replace=False)]
+    for b, h in units:
         hk = h // g
         ro, rl = oracle.sparse_decode_attn_shared(np_of(q[b:b + 1, h:h + 1]), np_of(K[b:b + 1, hk:hk + 1]),
                                                   np_of(V[b:b + 1, hk:hk + 1]), r_idx[b], r_cnt[b], cfg.dtype,
                                                   cfg.sm_scale)
-        assert float(np.abs(np_of(out[b, h]) - ro[0, 0]).max()) <= 2e-2
-        assert abs(float(lse[b, h]) - float(rl[0, 0])) <= 1e-4 * max(1.0, abs(float(rl[0, 0])))
+        assert_attention(np_of(out[b, h]), ro[0, 0], cfg.dtype, np_of(lse[b, h]), rl[0, 0])
 
 
 @pytest.mark.parametrize("B", [1, 8])  # per-head kernel / one workgroup per KV group
@@ -157,7 +156,7 @@ def test_headless_degenerate_lists(oracle, B):
     out, lse = shared_attn(q, K, V, idx, cnt, N, 0.2, 0, tail=(N - 5, N))
     r_idx = np.tile(np.arange(N - 5, N, dtype=np.int32), (B, 1))
     r_out, r_lse = oracle.sparse_decode_attn_shared(np_of(q), np_of(K), np_of(V), r_idx, np.full(B, 5, np.int32), "bf16", 0.2)
-    assert np.allclose(np_of(out), r_out, atol=2e-2, rtol=0) and np.allclose(np_of(lse), r_lse, atol=1e-3, rtol=1e-4)
+    assert_attention(np_of(out), r_out, "bf16", np_of(lse), r_lse)
     out, lse = shared_attn(q, K, V, idx, cnt, N, 0.2, 4)
     assert torch.all(out == 0) and torch.all(torch.isinf(lse) & (lse < 0))
 
@@ -202,5 +201,4 @@ def test_headless_interval_loop(oracle, B, mode):
         else:
             ro, rl, _, ucnt = drv.step(t, N_t, np_of(q), np_of(q_imp), Kn, Vn, Kin)
             assert np.array_equal(ucnt, drv.exp_cnt + (N_t - drv.N_pred))
-        assert float(np.abs(np_of(out) - ro).max()) <= 2e-2, f"step {t}"
-        assert np.abs(np_of(lse) - rl).max() <= 1e-3
+        assert_attention(np_of(out), ro, cfg.dtype, np_of(lse), rl, what=f"step {t}")

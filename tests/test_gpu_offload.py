@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import DEV, gpu_decode_step, gpu_project, np_of
+from gpu_util import DEV, assert_attention, assert_projection, gpu_decode_step, gpu_project, np_of, projection_magnitude
 from paper_2503_07518_amd import binding as tb
 
 pytestmark = pytest.mark.gpu
@@ -45,9 +45,9 @@ def test_decode_step_with_kv_in_pinned_host_memory(oracle):
     torch.cuda.synchronize()
     Kn, Vn, Kin = np_of(K), np_of(V), np_of(Kimp)
     ref_kimp = oracle.project_keys(Kn, np_of(W), "bf16")
+    assert_projection(oracle, Kin, ref_kimp, projection_magnitude(oracle, Kn, np_of(W), "bf16", Hkv), "bf16")
     assert np.mean(Kin == ref_kimp) > 0.99
     ridx, rcnt = oracle.select_topk(np_of(scores)[:, :, :N], k, 4, 16)
     assert np.array_equal(rcnt, np_of(cnt)) and np.array_equal(ridx, np_of(idx)[..., : ridx.shape[-1]])
     rout, rlse = oracle.sparse_decode_attn(np_of(q), Kn, Vn, np_of(idx), np_of(cnt), "bf16", 1.0 / math.sqrt(D))
-    assert np.abs(np_of(out) - rout).max() <= 2e-2
-    assert np.abs(np_of(lse) - rlse).max() <= 1e-3
+    assert_attention(np_of(out), rout, "bf16", np_of(lse), rlse)

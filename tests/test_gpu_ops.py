@@ -1,10 +1,8 @@
 """GPU parity: every exported operation, called through the C ABI, against the CPU oracle on
 the same bytes.  Sizes span several tiles and ragged tails; edge cases are listed per op.
 
-Bars: index lists bit-exact; scores within 1e-4 relative (with a magnitude guard for
-cancelled sums); attention within 1e-5 absolute (fp32) / 2e-2 absolute (bf16 K/V); projected
-keys within 1 unit in the last place of the storage type (fp32 accumulation against the
-oracle's fp64 accumulation can land on the other side of a rounding boundary)."""
+The bars (index lists bit-exact; scores, attention, log-sum-exp and projected keys within the
+tolerances of the benchmark definition) are stated once, in gpu_util.py."""
 import math
 
 import numpy as np
@@ -13,8 +11,9 @@ import torch
 
 pytestmark = pytest.mark.gpu
 
-from gpu_util import (DEV, dtype_name, gpu_attn, gpu_decode_step, gpu_expand, gpu_project, gpu_score, gpu_select,
-                      np_of, score_tolerance)
+from gpu_util import (ATTN_TOL, DEV, assert_attention, assert_projection, assert_scores, dtype_name, gpu_attn,
+                      gpu_decode_step, gpu_expand, gpu_project, gpu_score, gpu_select, np_of, projection_magnitude,
+                      score_magnitude)
 
 
 def say(msg):
@@ -58,18 +57,9 @@ def test_project_keys(oracle, dtype, D, Dimp, N, Hw):
     ref = oracle.project_keys(np_of(K)[:, :, :N], np_of(W), dn)
     got = np_of(Kimp)
     assert not got[:, :, N:].any(), "rows beyond N must stay untouched"
-    if dn == "f32":
-        r64 = ref.astype(np.float64)
-        mag = np.einsum("bhnd,hdj->bhnj", np.abs(np_of(K)[:, :, :N]).astype(np.float64),
-                        np.abs(np.broadcast_to(np_of(W), (Hkv,) + W.shape[1:])).astype(np.float64))
-        assert np.all(np.abs(got[:, :, :N] - r64) <= 1e-5 * mag + 1e-30)
-    else:
-        g64, r64 = oracle.bf16_to_f64(got[:, :, :N]), oracle.bf16_to_f64(ref)
-        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(r64), 2.0 ** -126))) - 7)
-        mag = np.einsum("bhnd,hdj->bhnj", np.abs(oracle.bf16_to_f64(np_of(K)[:, :, :N])),
-                        np.abs(np.broadcast_to(oracle.bf16_to_f64(np_of(W)), (Hkv,) + W.shape[1:])))
-        # one unit in the last place of the stored value plus the fp32-accumulation error of the sum
-        assert np.all(np.abs(g64 - r64) <= ulp * 1.0000001 + 1e-6 * mag)
+    mag = projection_magnitude(oracle, np_of(K)[:, :, :N], np_of(W), dn, Hkv)
+    assert_projection(oracle, got[:, :, :N], ref, mag, dn)
+    if dn == "bf16":
         assert np.mean(got[:, :, :N] == ref) > 0.99  # and nearly always the same bits
 
 
@@ -97,9 +87,9 @@ def test_project_strided_cache(oracle):
     Kimp = Kimp_big[:, :, :, :Dimp]
     gpu_project(K, W, N, Kimp=Kimp)
     torch.cuda.synchronize()
-    ref = oracle.bf16_to_f64(oracle.project_keys(np_of(K)[:, :, :N], np_of(W), "bf16"))
-    got = oracle.bf16_to_f64(np_of(Kimp)[:, :, :N])
-    assert np.allclose(got, ref, rtol=2 ** -7, atol=1e-30)
+    ref = oracle.project_keys(np_of(K)[:, :, :N], np_of(W), "bf16")
+    mag = projection_magnitude(oracle, np_of(K)[:, :, :N], np_of(W), "bf16", Hkv)
+    assert_projection(oracle, np_of(Kimp)[:, :, :N], ref, mag, "bf16")
     assert not np_of(Kimp_big)[..., Dimp:].any()
 
 
@@ -124,9 +114,7 @@ def test_score(oracle, dtype, B, Hq, Hkv, Dimp, N):
     dn = dtype_name(Kimp)
     ref = oracle.score(np_of(q_imp), np_of(Kimp)[:, :, :N], dn, scale)
     got = np_of(s)
-    guard = score_tolerance(oracle, np_of(q_imp), np_of(Kimp)[:, :, :N], dn, scale, Hq // Hkv)
-    err = np.abs(got[:, :, :N].astype(np.float64) - ref)
-    assert np.all(err <= 1e-4 * np.abs(ref) + guard)
+    assert_scores(got[:, :, :N], ref, score_magnitude(oracle, np_of(q_imp), np_of(Kimp)[:, :, :N], dn, Hq // Hkv), scale)
     assert np.isnan(got[:, :, N:]).all(), "padding beyond N must stay untouched"
 
 
@@ -313,9 +301,6 @@ def test_expand_neighbors(oracle, N, count_max, radius, mode):
 
 # --------------------------------------------------------------------------- attention
 
-ATTN_TOL = {"f32": 1e-5, "bf16": 2e-2}
-
-
 @pytest.mark.parametrize("dtype,B,Hq,Hkv,D,N,count_max", [
     (torch.float32, 1, 8, 8, 64, 1024, 128),
     (torch.bfloat16, 1, 32, 8, 128, 5000, 700),
@@ -338,11 +323,8 @@ def test_sparse_decode_attn(oracle, dtype, B, Hq, Hkv, D, N, count_max):
     dn = dtype_name(K)
     ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K)[:, :, :N], np_of(V)[:, :, :N], idx, cnt, dn, sm)
     go, gl = np_of(out), np_of(lse)
-    assert np.abs(go - ro).max() <= ATTN_TOL[dn]
+    assert_attention(go, ro, dn, gl, rl)
     assert not go[0, 0].any() and gl[0, 0] == -np.inf
-    fin = np.isfinite(rl)
-    assert np.array_equal(np.isfinite(gl), fin)
-    assert np.abs(gl[fin] - rl[fin]).max() <= 1e-4
 
 
 def test_attn_full_budget_equals_dense_and_tail(oracle):
@@ -357,7 +339,7 @@ def test_attn_full_budget_equals_dense_and_tail(oracle):
     out, _ = gpu_attn(q, K, V, full, cnt, N, sm)
     torch.cuda.synchronize()
     dense = oracle.dense_decode_attn(np_of(q), np_of(K), np_of(V), "bf16", sm)
-    assert np.abs(np_of(out) - dense).max() <= 2e-2
+    assert_attention(np_of(out), dense, "bf16", what="full list against dense attention")
     # a list over the first part plus the rest as a dense tail gives the same result
     idx, c = random_lists(B, Hq, 2000, 300, seed=18)
     out_t, lse_t = gpu_attn(q, K, V, torch.from_numpy(idx).to(DEV), torch.from_numpy(c).to(DEV), N, sm,
@@ -369,8 +351,7 @@ def test_attn_full_budget_equals_dense_and_tail(oracle):
         joined[0, h, : c[0, h]] = idx[0, h, : c[0, h]]
         joined[0, h, c[0, h]: c[0, h] + N - 2000] = np.arange(2000, N)
     ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K), np_of(V), joined, c + (N - 2000), "bf16", sm)
-    assert np.abs(np_of(out_t) - ro).max() <= 2e-2
-    assert np.abs(np_of(lse_t) - rl).max() <= 1e-4
+    assert_attention(np_of(out_t), ro, "bf16", np_of(lse_t), rl)
 
 
 def test_attn_strided_cache_and_max_count_truncation(oracle):
@@ -384,27 +365,48 @@ def test_attn_strided_cache_and_max_count_truncation(oracle):
     out, lse = gpu_attn(q, K, V, torch.from_numpy(idx).to(DEV), torch.from_numpy(cnt).to(DEV), N, sm, max_count=260)
     torch.cuda.synchronize()
     ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K), np_of(V), idx, np.minimum(cnt, 260), "bf16", sm)
-    assert np.abs(np_of(out) - ro).max() <= 2e-2
+    assert_attention(np_of(out), ro, "bf16", np_of(lse), rl)
 
 
-def test_attn_repeatable(oracle):
-    say("attn: repeated runs are bit-identical (fixed merge order)")
-    B, Hq, Hkv, D, N = 1, 32, 8, 128, 20000
+@pytest.mark.parametrize("B,Hq,Hkv,N,k", [(1, 32, 8, 32768, 3277), (16, 32, 8, 16384, 2048)])
+def test_attn_split_handover_repeatable(oracle, B, Hq, Hkv, N, k):
+    """The split attention hands partial results from workgroup to workgroup (last arriver
+    combines): 200 launches on the shapes of the single-sequence and the batched benchmark
+    configuration, each compared bit for bit with the first, which is checked against the
+    oracle.  Stops at the first mismatch."""
+    say(f"attn hand-over: 200 launches, B={B} Hq={Hq} N={N} k={k}")
+    D = 128
     q = randn((B, Hq, D), torch.bfloat16, 22)
     K = randn((B, Hkv, N, D), torch.bfloat16, 23)
     V = randn((B, Hkv, N, D), torch.bfloat16, 24)
-    idx, cnt = random_lists(B, Hq, N, 2000, seed=25)
+    rng = np.random.default_rng(25)  # full lists: the largest number of splits
+    idx = np.stack([np.stack([np.sort(rng.choice(N, k, replace=False)).astype(np.int32) for _ in range(Hq)])
+                    for _ in range(B)])
+    cnt = np.full((B, Hq), k, np.int32)
     ti, tc = torch.from_numpy(idx).to(DEV), torch.from_numpy(cnt).to(DEV)
     from paper_2503_07518_amd import binding as tb
     d = tb.make_desc(N, Hq, K=K, V=V)
-    ws = tb.new_workspace(tb.TB_OP_ATTN, d, 2000)
-    ref = None
-    for _ in range(5):
-        out, lse = gpu_attn(q, K, V, ti, tc, N, 0.09, ws=ws)
+    ws = tb.new_workspace(tb.TB_OP_ATTN, d, k)
+    sm = 1 / math.sqrt(D)
+    out, lse = gpu_attn(q, K, V, ti, tc, N, sm, ws=ws)
+    torch.cuda.synchronize()
+    ref = (out.clone(), lse.clone())
+    # the oracle on a sample of units (all of them for the single sequence)
+    rng = np.random.default_rng(7)
+    units = [(b, h) for b in range(B) for h in range(Hq)] if B == 1 else [
+        (int(rng.integers(B)), int(rng.integers(Hq))) for _ in range(64)]
+    g = Hq // Hkv
+    for b, h in units:
+        ro, rl = oracle.sparse_decode_attn(np_of(q[b:b + 1, h:h + 1]), np_of(K[b:b + 1, h // g:h // g + 1]),
+                                           np_of(V[b:b + 1, h // g:h // g + 1]), idx[b:b + 1, h:h + 1],
+                                           cnt[b:b + 1, h:h + 1], "bf16", sm)
+        assert_attention(np_of(out[b, h]), ro[0, 0], "bf16", np_of(lse[b, h]), rl[0, 0])
+    for it in range(200):
+        out, lse = gpu_attn(q, K, V, ti, tc, N, sm, ws=ws)
+        if it % 20 == 19:
+            print(f"[case]   launch {it + 1}", flush=True)
         torch.cuda.synchronize()
-        if ref is None:
-            ref = (out.clone(), lse.clone())
-        assert torch.equal(out, ref[0]) and torch.equal(lse, ref[1])
+        assert torch.equal(out, ref[0]) and torch.equal(lse, ref[1]), f"launch {it} differs from the first"
 
 
 # --------------------------------------------------------------------------- fused step
@@ -438,7 +440,7 @@ def test_decode_step_matches_separate_calls_and_oracle(oracle, dtype, B, Hq, Hkv
     assert np.array_equal(np_of(cnt), rcnt)
     assert np.array_equal(np_of(idx)[..., : ridx.shape[-1]], ridx)
     ro, rl = oracle.sparse_decode_attn(np_of(q), np_of(K), np_of(V), np_of(idx), np_of(cnt), dn, sm)
-    assert np.abs(np_of(out) - ro).max() <= ATTN_TOL[dn]
+    assert_attention(np_of(out), ro, dn, np_of(lse), rl)
 
 
 def test_read_stream_probe_reads_and_writes_nothing():

@@ -530,6 +530,60 @@ def test_interval_driver_reduces_to_per_step_path_and_set_sizes(oracle):
                 assert np.all(np.diff(got) > 0) and got[-1] == N_t - 1
 
 
+def test_interval_driver_expand_on_predict(oracle):
+    """Sec. 3.4, neighbour fetching "per prediction step": with expand_on_predict the prediction
+    step itself attends over the widened selection.  Pins: the list it uses is exactly
+    expand(select(scores)); its length is |expand(sel)| (between k and (2r+1)k, and 2k for the
+    cluster rule away from the end of the cache); with P = 1 every step is such a step and the
+    output equals attention over the widened set computed by hand from the separate calls; the
+    reuse steps are unchanged by the flag."""
+    rng = np.random.default_rng(21)
+    B, Hq, Hkv, N0, D, d, k, steps = 2, 4, 2, 150, 16, 8, 10, 7
+    Ncap = N0 + steps
+    K = rng.standard_normal((B, Hkv, Ncap, D)).astype(np.float32)
+    V = rng.standard_normal((B, Hkv, Ncap, D)).astype(np.float32)
+    W = (rng.standard_normal((1, D, d)) / 4).astype(np.float32)
+    Kimp = oracle.project_keys(K, W, "f32")
+    qs = rng.standard_normal((steps, B, Hq, D)).astype(np.float32)
+    qis = rng.standard_normal((steps, B, Hq, d)).astype(np.float32)
+    for mode, radius in ((0, 1), (0, 2), (1, 1)):
+        # P = 1: every step predicts, widens and attends over the widened set
+        drv = oracle.IntervalDriver("f32", k, P=1, radius=radius, sink=1, window=2, sm_scale=0.25,
+                                    expand_on_predict=True, mode=mode)
+        for t in range(steps):
+            N_t = N0 + t
+            out, lse, idx, cnt = drv.step(t, N_t, qs[t], qis[t], K, V, Kimp)
+            s = oracle.score(qis[t], Kimp[:, :, :N_t], "f32", 1.0)
+            sel, scnt = oracle.select_topk(s, k, 1, 2)
+            eidx, ecnt = oracle.expand_neighbors(sel, scnt, N_t, radius, mode=mode)
+            assert np.array_equal(cnt, ecnt)
+            m = np.arange(eidx.shape[-1])[None, None] < ecnt[..., None]
+            assert np.array_equal(np.where(m, idx, -1), np.where(m, eidx, -1))
+            out2, lse2 = oracle.sparse_decode_attn(qs[t], K[:, :, :N_t], V[:, :, :N_t], eidx, ecnt, "f32", 0.25)
+            assert np.array_equal(out, out2) and np.array_equal(lse, lse2)
+            n_sel = int(scnt[0, 0])
+            if mode == 0:
+                assert np.all(ecnt >= n_sel) and np.all(ecnt <= (2 * radius + 1) * n_sel)
+            else:
+                assert np.all(ecnt <= 2 * n_sel) and np.all(ecnt >= n_sel)
+            # every selected token is in the widened list
+            for b in range(B):
+                for h in range(Hq):
+                    assert set(sel[b, h, : scnt[b, h]]) <= set(idx[b, h, : cnt[b, h]])
+    # P = 3: the flag changes the prediction steps only
+    a = oracle.IntervalDriver("f32", k, P=3, radius=1, sm_scale=0.25, expand_on_predict=True)
+    c = oracle.IntervalDriver("f32", k, P=3, radius=1, sm_scale=0.25, expand_on_predict=False)
+    for t in range(steps):
+        N_t = N0 + t
+        oa, la, ia, ca = a.step(t, N_t, qs[t], qis[t], K, V, Kimp)
+        oc, lc, ic, cc = c.step(t, N_t, qs[t], qis[t], K, V, Kimp)
+        if t % 3 == 0:
+            assert np.array_equal(ca, a.exp_cnt) and np.all(ca >= cc) and np.all(cc == k)
+            assert not np.array_equal(oa, oc)  # more rows attended: a different output
+        else:
+            assert np.array_equal(ca, cc) and np.array_equal(oa, oc) and np.array_equal(la, lc)
+
+
 # --------------------------------------------------------------------------- buffer migration
 
 def test_gather_kv_rows_are_copies_in_list_order(oracle):
@@ -595,3 +649,21 @@ def test_predict_queries_against_library_layers_and_closed_forms(oracle):
     qb, _ = oracle.predict_queries(*(oracle.to_numpy(torch.from_numpy(a).bfloat16()) for a in (h, gamma, beta, W1, b1, W2, b2)),
                                    G, Hq, Dimp, "bf16")
     assert qb.dtype == np.uint16 and qb.shape == (G, B, Hq, Dimp)
+    # ... checked value by value against torch's own fp64 layers on the bf16-rounded inputs and
+    # torch's own fp64 -> bf16 conversion (round to nearest even): identical bit patterns, except
+    # where the fp64 result lies within 1e-9 (relative) of the midpoint between two bf16 values
+    # and the two fp64 evaluations may fall on different sides of it
+    tb16 = lambda a: torch.from_numpy(a).bfloat16().double()
+    xb = F.layer_norm(tb16(h), (E,), tb16(gamma), tb16(beta), 1e-5)
+    yb = F.linear(F.gelu(F.linear(xb, tb16(W1), tb16(b1))), tb16(W2), tb16(b2))
+    yb = yb.reshape(B, G, Hq, Dimp).permute(1, 0, 2, 3).contiguous()
+    want = yb.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    diff = qb != want
+    if diff.any():
+        lo64 = np.minimum(oracle.bf16_to_f64(qb), oracle.bf16_to_f64(want))
+        hi64 = np.maximum(oracle.bf16_to_f64(qb), oracle.bf16_to_f64(want))
+        mid = 0.5 * (lo64 + hi64)
+        assert np.all(np.abs(yb.numpy() - mid)[diff] <= 1e-9 * np.abs(mid)[diff]), "bf16 predictor output off by more than a tie"
+    assert diff.mean() < 0.01
+    # a planted mistake must show: a wrong slot order or a dropped bias changes most values
+    assert (oracle.bf16_to_f64(qb) != oracle.bf16_to_f64(qb[::-1])).mean() > 0.9
