@@ -27,9 +27,21 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X datasheet HBM3E bandwidth
 
-# HBM bytes per launch of the gather-attention kernel measured with rocprofv3 PMC counters
-# (FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB device copy; profiles/decode_step_C2_hbm_traffic.txt)
-MEASURED_ATTN_TRAFFIC = {"C2_llama3_8b_32k": 46.97e6 + 0.35e6}
+
+
+def measured_traffic(cfg_name, kernel, what="decode_step"):
+    """HBM bytes per launch of `kernel` on this configuration, as measured with rocprofv3 PMC
+    counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a 256 MiB
+    device copy): read from the summary of those runs under profiles/, None when there is none."""
+    path = os.path.join(ROOT, "profiles", f"{what}_{cfg_name.split('_')[0]}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
 
 
 def parse_args():
@@ -49,6 +61,9 @@ def parse_args():
     ap.add_argument("--no-headless", action="store_true",
                     help="skip the timings of the head-less variant (keeps a profile of the per-head kernels clean)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--only-reuse-step", action="store_true",
+                    help="interval configurations: run the loop once, then time (and, under a profiler, expose) only "
+                         "the attention launch of a reuse step; prints that record and exits")
     return ap.parse_args()
 
 
@@ -88,7 +103,7 @@ class LayerBuffers:
         return sum(t.numel() * t.element_size() for t in (self.K, self.V, self.Kimp, self.scores, self.idx))
 
 
-def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False, mode=0):
+def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False, mode=0, reuse_launches=20):
     """The prediction-interval loop of the config (cfg.steps decode steps, a prediction every
     cfg.P steps, neighbours of radius cfg.radius on the steps in between) as one HIP graph:
     mean time per step, and the rows that attention gathers on the two kinds of step.
@@ -138,7 +153,7 @@ def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False, mod
     N_last = cfg.N + t_last
     desc = tb.make_desc(N_last, cfg.Hq, K=K, V=V, Kimp=Kimp)
     e0.record(cur)
-    for _ in range(20):
+    for _ in range(reuse_launches):
         if buffered:
             tb.tb_buffered_decode_attn(desc, qs[t_last], dec.Kbuf, dec.Vbuf, dec.exp_cnt, dec.exp_cap, K, V,
                                        cfg.sm_scale, dec.out, dec.lse, dec.ws, tail_begin=dec.N_pred, tail_end=N_last)
@@ -147,7 +162,7 @@ def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False, mod
                                      dec.out, dec.lse, dec.ws, tail_begin=dec.N_pred, tail_end=N_last)
     e1.record(cur)
     torch.cuda.synchronize()
-    us_reuse = e0.elapsed_time(e1) * 1e3 / 20
+    us_reuse = e0.elapsed_time(e1) * 1e3 / reuse_launches
     reuse_bytes = (exp_rows + cfg.B * cfg.Hq * (N_last - dec.N_pred)) * 2 * cfg.D * cfg.elt_bytes
     us_migrate = None
     if buffered:
@@ -186,6 +201,13 @@ def main():
     torch.cuda.set_device(0)
     tb.load_library()
     cfg = {**workloads.CONFIGS, **workloads.EXTRA_CONFIGS}[args.config]
+    if args.only_reuse_step:
+        assert cfg.P > 1, "--only-reuse-step needs a configuration with a prediction interval"
+        rec = time_interval_loop(cfg, tb, workloads, torch, replays=1, reuse_launches=40)
+        rec["reuse_step"]["traffic"] = measured_traffic(cfg.name, "attn_kernel", what="reuse_step")
+        print(json.dumps({"metric": "reuse_step_attention_latency", "value": rec["reuse_step"]["us"], "unit": "us/step",
+                          "n_gpus": 1, "config": {"workload": cfg.name + " (reuse step)"}, "interval_loop": rec}))
+        return
 
     # ---- buffers: enough distinct copies that a step never finds its data in the last-level cache
     probe = LayerBuffers(cfg, 0, tb, workloads, torch, args.kv_layout, args.kv_host)
@@ -350,7 +372,7 @@ def main():
         stage_select(b)
 
     us_pre = timer(stage_score_select)
-    us_attn_step = max(us_step - us_pre, 1e-3)
+    us_attn_step = max(us_step - us_pre, 1e-3)  # (a nonsensical difference is flagged as roofline.suspect)
     us_proj = timer(stage_project_append)
     # (with the cache in host memory the batched projection would time the host link, not the kernel)
     us_proj_bulk = timer(stage_project_bulk) if not args.kv_host else float("inf")
@@ -455,12 +477,23 @@ def main():
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(proj_gbps / HBM_PEAK_GBPS, 4),
             "tflops": round(2.0 * cfg.B * cfg.Hkv * cfg.N * cfg.D * cfg.Dimp / us_proj_bulk / 1e6, 1),
         },
+        # the dominant kernel of the step.  `us` is its duration inside the step (step minus the
+        # step without it), which is what the profiler's in-step duration shows; launched back to
+        # back on its own it can be faster (rows found again in the last-level cache).  The whole
+        # step against the same peak is in `step` (and in step_hbm above).
         "roofline": {
             "kernel": "attn_kernel (tb_sparse_decode_attn)", "bound": "hbm", "achieved": round(attn_gbps, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
             "algorithmic_bytes": bytes_gather, "us": round(us_attn_step, 3),
-            "timing": "inside the step: step minus (score + select); back to back on its own: stages_us.sparse_attn",
-            "traffic": MEASURED_ATTN_TRAFFIC.get(cfg.name),
+            "us_back_to_back": round(us_attn, 3),
+            "frac_back_to_back": round(bytes_gather / us_attn / 1e3 / HBM_PEAK_GBPS, 4),
+            "timing": "us: inside the step (step minus score + select); us_back_to_back: launched on its own",
+            "traffic": measured_traffic(cfg.name, "attn_kernel"),
+            "step": {"us": round(us_step, 3), "algorithmic_bytes": bytes_step, "achieved": round(step_gbps, 1),
+                     "frac": round(step_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic(cfg.name, "step")},
+            # a difference of two noisy timings: flagged when it cannot be right
+            "suspect": bool(us_attn_step <= 0.5 * us_attn or attn_gbps > HBM_PEAK_GBPS),
         },
         # head-less selection (one list per batch element for all heads): scoring and selection
         # of one importance head, attention over the shared list
@@ -517,6 +550,7 @@ def main():
         del stack
     if cfg.P > 1:
         result["interval_loop"] = time_interval_loop(cfg, tb, workloads, torch)
+        result["interval_loop"]["reuse_step"]["traffic"] = measured_traffic(cfg.name, "attn_kernel", what="reuse_step")
         result["interval_loop_buffered"] = time_interval_loop(cfg, tb, workloads, torch, buffered=True)
         result["interval_loop_cluster_neighbours"] = time_interval_loop(cfg, tb, workloads, torch, mode=1)
 

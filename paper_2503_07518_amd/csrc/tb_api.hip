@@ -50,10 +50,11 @@ bool attn_shared_list_grouped(const tb_cache_desc* d) {
 
 SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk) {
   SelectPlan p{1, 0, 0, 2};
-  // worth it when the row is long and the budget a small share of the candidates (the kept keys
-  // are then a small share of the row as well); measured on 16K..64K rows, two launches cost
-  // more than the one-workgroup selection
-  if (units <= 0 || kk <= 0 || N < 131072 || kk * 8 > candidates) return p;
+  // worth it when the budget is a small share of the candidates (the kept keys are then a small
+  // share of the row as well) and the row is longer than the 65536 scores one workgroup holds in
+  // registers (beyond that it would stream the row again in every phase: 44 against 27 us just
+  // past 65536); up to 65536 scores two launches cost more than the one-workgroup selection
+  if (units <= 0 || kk <= 0 || N <= 65536 || kk * 8 > candidates) return p;
   int64_t len = 32768;
   if (units * ((N + len - 1) / len) > 512) len = 65536;   // at most two rounds of workgroups on 256 compute units
   // few rows (a head-less selection has one per batch element): more, shorter pieces, so that

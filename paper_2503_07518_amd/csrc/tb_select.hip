@@ -728,8 +728,8 @@ __device__ __forceinline__ void piece_body(const SelectArgs& a, const int u, con
   const float* s = row + base;
   const int64_t last4 = n_c > 0 ? ((n_c - 1) & ~int64_t{3}) : 0;
   const int64_t wbase = static_cast<int64_t>(wave) * NT * kWaveTile + lane * 4;
-  // the sample of the whole row: the first of four adjacent scores at each of `kThreads` positions
-  // spread evenly over the candidates
+  // the sample of the whole row: four adjacent scores at each of `kThreads` positions spread
+  // evenly over the candidates
   const int64_t span = a.hi - a.lo;
   const int64_t sp = (a.lo + (tid * span) / kThreads) & ~int64_t{3};
   const int64_t row_last4 = (a.N - 1) & ~int64_t{3};
@@ -753,10 +753,14 @@ __device__ __forceinline__ void piece_body(const SelectArgs& a, const int u, con
   {
     uint32_t sk[4];
     keys_of4(sraw, a.lo, a.hi, sp, sk);  // (the four may straddle an end of the candidate range)
-    uint32_t ks = sk[0] ? sk[0] : (sk[1] ? sk[1] : (sk[2] ? sk[2] : sk[3]));
-    if (ks) {
-      atomicAdd(&s_hist[ks >> kTopShift], 1u);
-      n_valid = 1;
+    // all four enter the histogram (4096 keys): a piece does little else, and a narrower bracket
+    // means fewer kept keys to store and to select among
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (sk[i]) {
+        atomicAdd(&s_hist[sk[i] >> kTopShift], 1u);
+        ++n_valid;
+      }
     }
   }
   uint32_t b_lo, b_hi;
