@@ -103,7 +103,8 @@ class LayerBuffers:
         return sum(t.numel() * t.element_size() for t in (self.K, self.V, self.Kimp, self.scores, self.idx))
 
 
-def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False, mode=0, reuse_launches=20):
+def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False, mode=0, reuse_launches=20,
+                       ring=0, sink=None, window=None, expand_on_predict=False):
     """The prediction-interval loop of the config (cfg.steps decode steps, a prediction every
     cfg.P steps, neighbours of radius cfg.radius on the steps in between) as one HIP graph:
     mean time per step, and the rows that attention gathers on the two kinds of step.
@@ -118,11 +119,21 @@ def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False, mod
     qs = [data["q"][t].contiguous() for t in range(cfg.steps)]
     qis = [data["q_imp"][t].contiguous() for t in range(cfg.steps)]
 
-    dec = interval.IntervalDecoder(K, V, W, Kimp, cfg.Hq, cfg.k, cfg.P, cfg.radius, sink=cfg.sink,
-                                   window=cfg.window, sm_scale=cfg.sm_scale, buffered=buffered, mode=mode)
+    sink = cfg.sink if sink is None else sink
+    window = cfg.window if window is None else window
+    if ring:
+        # the paper's three physical buffers (sink, local-window ring, important buffer) with the
+        # projection deferred to the wraps of the ring
+        dec = interval.RingLayoutDecoder(K, V, W, Kimp, cfg.Hq, cfg.k, cfg.P, cfg.radius, ring, sink=sink,
+                                         sm_scale=cfg.sm_scale, mode=mode)
+    else:
+        dec = interval.IntervalDecoder(K, V, W, Kimp, cfg.Hq, cfg.k, cfg.P, cfg.radius, sink=sink, window=window,
+                                       sm_scale=cfg.sm_scale, buffered=buffered, mode=mode,
+                                       expand_on_predict=expand_on_predict)
 
     def loop():
-        dec.N_pred = dec.projected_upto = None  # the cache is back at its post-prefill length
+        if not ring:
+            dec.N_pred = dec.projected_upto = None  # the cache is back at its post-prefill length
         for t in range(cfg.steps):
             dec.step(t, cfg.N + t, qs[t], qis[t])
 
@@ -148,6 +159,12 @@ def time_interval_loop(cfg, tb, workloads, torch, replays=5, buffered=False, mod
     torch.cuda.synchronize()
     us_loop = e0.elapsed_time(e1) * 1e3 / replays
     n_pred = -(-cfg.steps // cfg.P)
+    if ring:
+        return {"attention_reads": "sink buffer + local-window ring + important buffer", "ring": ring, "sink": sink,
+                "steps": cfg.steps, "P": cfg.P, "radius": cfg.radius, "prediction_steps": n_pred,
+                "batched_projections": dec.projections // 2,  # (the loop ran twice on the host: eagerly and under capture)
+                "us_per_step_mean": round(us_loop / cfg.steps, 3), "us_loop": round(us_loop, 1),
+                "rows_in_important_buffers": int(dec.imp_cnt.sum().item())}
     # one reuse step on its own (attention over the widened list + the rows appended since)
     t_last = cfg.steps - 1
     N_last = cfg.N + t_last
@@ -553,6 +570,11 @@ def main():
         result["interval_loop"]["reuse_step"]["traffic"] = measured_traffic(cfg.name, "attn_kernel", what="reuse_step")
         result["interval_loop_buffered"] = time_interval_loop(cfg, tb, workloads, torch, buffered=True)
         result["interval_loop_cluster_neighbours"] = time_interval_loop(cfg, tb, workloads, torch, mode=1)
+        # the paper's layout in full (128 sink tokens, a ring of 256) against the fused gather under
+        # the same policy (sink 128, window 256, the widened list attended on prediction steps too)
+        result["interval_loop_ring_layout"] = time_interval_loop(cfg, tb, workloads, torch, ring=256, sink=128)
+        result["interval_loop_fused_same_policy"] = time_interval_loop(cfg, tb, workloads, torch, sink=128, window=256,
+                                                                       expand_on_predict=True)
 
     if not args.no_cpu_baseline:
         import numpy as np

@@ -150,6 +150,18 @@ tb_status tb_gather_kv(const tb_cache_desc* desc, const void* K, const void* V, 
                        const int32_t* count, int64_t idx_cap, int64_t max_count, void* Kbuf, void* Vbuf,
                        int64_t buf_cap, void* stream);
 
+/* tb_gather_kv for the layout with a Sink Buffer and a Local Window Buffer of their own (Sec. 3.3
+ * "Inference Setup"): a list made by tb_select_topk (and widened by tb_expand_neighbors) begins
+ * with the sink positions and ends with the local-window positions; those rows live in their own
+ * buffers, so only the entries in between are migrated:
+ *   Kbuf/Vbuf[b,h,i,:] = K/V[b,h/g,idx[b,h,skip_front + i],:]   for 0 <= i < count_out[b,h],
+ *   count_out[b,h] = max(0, min(count[b,h], max_count) - skip_front - skip_back).
+ * buf_cap >= max(0, max_count - skip_front - skip_back); count_out: int32 [B][Hq], always written. */
+tb_status tb_gather_important(const tb_cache_desc* desc, const void* K, const void* V, const int32_t* idx,
+                              const int32_t* count, int64_t idx_cap, int64_t max_count, int32_t skip_front,
+                              int32_t skip_back, void* Kbuf, void* Vbuf, int64_t buf_cap, int32_t* count_out,
+                              void* stream);
+
 /* tb_sparse_decode_attn over rows that tb_gather_kv has migrated: the rows 0 .. count[b,h]-1 of
  * the per-query-head buffers (no index list is read) followed by the dense range
  * [tail_begin, tail_end) of the cache K, V (the local window of tokens appended since the

@@ -298,13 +298,26 @@ class IntervalDriver:
 
     def __init__(self, dtype, k: int, P: int, radius: int, sink: int = 0, window: int = 0,
                  sm_scale: float = 1.0, scale: float = 1.0, expand_on_predict: bool = False, mode: int = 0,
-                 headless: bool = False):
+                 headless: bool = False, ring: int = 0):
         self.dtype, self.k, self.P, self.radius = dtype, k, P, radius
         self.sink, self.window, self.sm_scale, self.scale = sink, window, sm_scale, scale
         self.expand_on_predict, self.mode = expand_on_predict, mode
         # head-less variant (Appendix "Additional Efficiency Evaluation"): q_imp [B,1,d'], Kimp
         # [B,1,N,d']; one list per batch element, attended by every head
         self.headless = headless
+        # ring > 0: the three-buffer layout of Sec. 3.3 "Inference Setup" with a Local Window
+        # Buffer of `ring` tokens (replaces `window`).  Starting from the post-prefill state the
+        # window fills over the first `ring` steps, so at step t it holds the W_t = min(ring, t)
+        # newest tokens; those are attended on EVERY step without a score and are no candidates.
+        # A prediction step selects among [sink, N_t - W_t), widens the list and attends over the
+        # widened list (the Important Buffer holds the widened selection); the other steps attend
+        # over the stored widened list WITHOUT the window rows of the prediction step, followed by
+        # the window as it is now -- rows that have left the window since the prediction and were
+        # not selected are not attended until the next prediction.
+        self.ring = ring
+        assert ring == 0 or (ring >= P and window == 0), "the window must cover a prediction interval"
+        self.N0 = None
+        self.W_pred = 0
         self.N_pred = None
         self.exp_idx = None
         self.exp_cnt = None
@@ -313,21 +326,29 @@ class IntervalDriver:
         """The token lists that step t attends over: (idx, count).  On a prediction step the
         scores and the selection are made (and the widened selection is stored); on the other
         steps the stored widened list is followed by the tokens appended since the prediction."""
+        if self.N0 is None:
+            self.N0 = N_t - t
+        W_t = min(self.ring, N_t - self.N0) if self.ring else self.window
         if t % self.P == 0:
             s = score(q_imp, np.ascontiguousarray(Kimp[:, :, :N_t]), self.dtype, self.scale)
-            sel, cnt = select_topk(s, self.k, self.sink, self.window)
-            self.N_pred = N_t
+            sel, cnt = select_topk(s, self.k, self.sink, W_t)
+            self.N_pred, self.W_pred = N_t, W_t
             self.exp_idx, self.exp_cnt = expand_neighbors(sel, cnt, N_t, self.radius, mode=self.mode)
-            return (self.exp_idx, self.exp_cnt) if self.expand_on_predict else (sel, cnt)
-        extra = N_t - self.N_pred
+            return (self.exp_idx, self.exp_cnt) if (self.expand_on_predict or self.ring) else (sel, cnt)
         B, Hq = self.exp_cnt.shape
+        if self.ring:
+            # widened list minus its last W_pred entries (the window rows of the prediction step:
+            # the largest positions of the list), then the window of this step
+            drop, tail = self.W_pred, np.arange(N_t - W_t, N_t, dtype=np.int32)
+        else:
+            drop, tail = 0, np.arange(self.N_pred, N_t, dtype=np.int32)
+        extra = len(tail)
         cap = self.exp_idx.shape[-1] + extra
         use_idx = np.full((B, Hq, cap), -1, dtype=np.int32)
-        use_cnt = self.exp_cnt + extra
-        tail = np.arange(self.N_pred, N_t, dtype=np.int32)
+        use_cnt = self.exp_cnt - drop + extra
         for b in range(B):
             for h in range(Hq):
-                c = int(self.exp_cnt[b, h])
+                c = int(self.exp_cnt[b, h]) - drop
                 use_idx[b, h, :c] = self.exp_idx[b, h, :c]
                 use_idx[b, h, c:c + extra] = tail
         return use_idx, use_cnt

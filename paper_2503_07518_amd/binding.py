@@ -23,7 +23,7 @@ TB_OP_SELECT, TB_OP_ATTN, TB_OP_DECODE_STEP = 1, 2, 3
 EXPORTS = (
     "tb_project_keys", "tb_score", "tb_select_topk", "tb_expand_neighbors", "tb_sparse_decode_attn",
     "tb_sparse_decode_attn_shared", "tb_sparse_decode_attn_static",
-    "tb_gather_kv", "tb_buffered_decode_attn", "tb_predict_queries", "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_read_stream_probe", "tb_status_string", "tb_version",
+    "tb_gather_kv", "tb_gather_important", "tb_buffered_decode_attn", "tb_predict_queries", "tb_decode_step", "tb_workspace_bytes", "tb_workspace_init", "tb_read_stream_probe", "tb_status_string", "tb_version",
 )
 
 
@@ -75,6 +75,7 @@ def load_library() -> ctypes.CDLL:
     L.tb_decode_step.argtypes = [dp, vp, vp, f32, vp, vp, vp, i32, i32, i32, f32, vp, i64, vp, vp, i64, vp, vp,
                                  vp, sz, vp]
     L.tb_gather_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, vp, vp, i64, vp]
+    L.tb_gather_important.argtypes = [dp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, i64, vp, vp]
     L.tb_buffered_decode_attn.argtypes = [dp, vp, vp, vp, i64, vp, i64, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
     L.tb_predict_queries.argtypes = [ctypes.POINTER(tb_predictor_desc), i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.tb_workspace_bytes.argtypes = [i32, dp, i64]
@@ -192,6 +193,14 @@ def tb_gather_kv(desc, K, V, idx, count, max_count: int, Kbuf, Vbuf, stream=None
     _check(load_library().tb_gather_kv(ctypes.byref(desc), _ptr(K), _ptr(V), _ptr(idx), _ptr(count), idx.stride(-2),
                                        max_count, _ptr(Kbuf), _ptr(Vbuf), Kbuf.shape[2], _stream(stream)),
            "tb_gather_kv")
+
+
+def tb_gather_important(desc, K, V, idx, count, max_count: int, skip_front: int, skip_back: int, Kbuf, Vbuf,
+                        count_out, stream=None) -> None:
+    assert Kbuf.is_contiguous() and Vbuf.is_contiguous() and Kbuf.shape == Vbuf.shape
+    _check(load_library().tb_gather_important(ctypes.byref(desc), _ptr(K), _ptr(V), _ptr(idx), _ptr(count),
+                                              idx.stride(-2), max_count, skip_front, skip_back, _ptr(Kbuf), _ptr(Vbuf),
+                                              Kbuf.shape[2], _ptr(count_out), _stream(stream)), "tb_gather_important")
 
 
 def tb_buffered_decode_attn(desc, q, Kbuf, Vbuf, count, max_count: int, K, V, sm_scale: float, out, lse, ws,

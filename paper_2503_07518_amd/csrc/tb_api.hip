@@ -342,6 +342,27 @@ tb_status tb_gather_kv(const tb_cache_desc* d, const void* K, const void* V, con
   return launch_gather(L, static_cast<hipStream_t>(stream));
 }
 
+tb_status tb_gather_important(const tb_cache_desc* d, const void* K, const void* V, const int32_t* idx,
+                              const int32_t* count, int64_t idx_cap, int64_t max_count, int32_t skip_front,
+                              int32_t skip_back, void* Kbuf, void* Vbuf, int64_t buf_cap, int32_t* count_out,
+                              void* stream) {
+  TB_TRY(check_desc(d));
+  if (!K || !V || !idx || !count || !Kbuf || !Vbuf || !count_out) return TB_ERR_INVALID_ARG;
+  if (idx_cap < 0 || max_count < 0 || max_count > idx_cap || skip_front < 0 || skip_back < 0) return TB_ERR_INVALID_ARG;
+  const int64_t rows = max_count > static_cast<int64_t>(skip_front) + skip_back ? max_count - skip_front - skip_back : 0;
+  if (rows > buf_cap) return TB_ERR_INVALID_ARG;
+  if (d->N == 0 && max_count > 0) return TB_ERR_INVALID_ARG;
+  TB_TRY(check_strides(d, d->k_stride_b, d->k_stride_h, d->k_stride_n, d->D));
+  TB_TRY(check_strides(d, d->v_stride_b, d->v_stride_h, d->v_stride_n, d->D));
+  if (!aligned16(K) || !aligned16(V) || !aligned16(Kbuf) || !aligned16(Vbuf)) return TB_ERR_UNSUPPORTED;
+  if (max_count > (int64_t{1} << 30)) return TB_ERR_UNSUPPORTED;
+  GatherLaunch L{d, K, V, idx, count, idx_cap, max_count, Kbuf, Vbuf, buf_cap};
+  L.skip_front = skip_front;
+  L.skip_back = skip_back;
+  L.count_out = count_out;
+  return launch_gather(L, static_cast<hipStream_t>(stream));
+}
+
 tb_status tb_buffered_decode_attn(const tb_cache_desc* d, const void* q, const void* Kbuf, const void* Vbuf,
                                   int64_t buf_cap, const int32_t* count, int64_t max_count, const void* K,
                                   const void* V, int64_t tail_begin, int64_t tail_end, float sm_scale, float* out,

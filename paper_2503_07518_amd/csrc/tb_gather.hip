@@ -1,5 +1,7 @@
 // Migration of the selected K/V rows into per-query-head "important" buffers (the paper's
-// physical layout, Sec. 3.3): Kbuf/Vbuf[b,h,i,:] = K/V[b,h/g,idx[b,h,i],:] for i < count[b,h].
+// physical layout, Sec. 3.3): Kbuf/Vbuf[b,h,i,:] = K/V[b,h/g,idx[b,h,skip_front + i],:] for
+// i < count[b,h] - skip_front - skip_back (the entries at the two ends of a list are the sink
+// prefix and the local window, which live in buffers of their own).
 // A pure copy: LPR = D*sizeof(T)/16 adjacent lanes move one row with a 128-bit load and store
 // each; a thread issues the loads of all its rows (K and V) before the first store.
 #include "tb_device.h"
@@ -23,6 +25,8 @@ struct GatherArgs {
   void* Vbuf;
   int64_t buf_cap;
   int32_t Hq, g;
+  int32_t skip_front, skip_back;  // list entries left out at the two ends
+  int32_t* count_out;             // nullable: receives the number of rows migrated per (b,h)
 };
 
 template <typename T, int D>
@@ -38,9 +42,12 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
   const int hkv = h / a.g;
   int64_t cnt = a.count[u];
   cnt = cnt < 0 ? 0 : (cnt > a.max_count ? a.max_count : cnt);
+  cnt -= a.skip_front + a.skip_back;
+  cnt = cnt < 0 ? 0 : cnt;
+  if (a.count_out && blockIdx.x == 0 && tid == 0) a.count_out[u] = static_cast<int32_t>(cnt);
   const int64_t i0 = static_cast<int64_t>(blockIdx.x) * RPP * kGatherRowsPerThread + rsub;
   if (i0 - rsub >= cnt) return;
-  const int32_t* list = a.idx + u * a.idx_cap;
+  const int32_t* list = a.idx + u * a.idx_cap + a.skip_front;
   const T* kb = static_cast<const T*>(a.K) + b * a.k_stride_b + hkv * a.k_stride_h + sub * EPL;
   const T* vb = static_cast<const T*>(a.V) + b * a.v_stride_b + hkv * a.v_stride_h + sub * EPL;
   T* ko = static_cast<T*>(a.Kbuf) + u * a.buf_cap * D + sub * EPL;
@@ -86,8 +93,13 @@ tb_status launch_td(const GatherLaunch& L, hipStream_t st) {
   a.buf_cap = L.buf_cap;
   a.Hq = d.Hq;
   a.g = d.Hq / d.Hkv;
+  a.skip_front = L.skip_front;
+  a.skip_back = L.skip_back;
+  a.count_out = L.count_out;
   constexpr int rows_per_wg = kGatherThreads / (D / Pack16<T>::kElts) * kGatherRowsPerThread;
-  dim3 grid(static_cast<unsigned>((L.max_count + rows_per_wg - 1) / rows_per_wg), d.Hq, d.B);
+  // (at least one workgroup per list, so that count_out is written for an empty one too)
+  const int64_t rows = L.max_count > L.skip_front + L.skip_back ? L.max_count - L.skip_front - L.skip_back : 1;
+  dim3 grid(static_cast<unsigned>((rows + rows_per_wg - 1) / rows_per_wg), d.Hq, d.B);
   hipLaunchKernelGGL((gather_kernel<T, D>), grid, dim3(kGatherThreads), 0, st, a);
   return hip_status(hipGetLastError());
 }
@@ -96,7 +108,7 @@ tb_status launch_td(const GatherLaunch& L, hipStream_t st) {
 
 tb_status launch_gather(const GatherLaunch& L, hipStream_t st) {
   const tb_cache_desc& d = *L.desc;
-  if (d.B == 0 || d.Hq == 0 || L.max_count == 0) return TB_OK;
+  if (d.B == 0 || d.Hq == 0 || (L.max_count == 0 && !L.count_out)) return TB_OK;
   if (d.dtype == TB_F32) {
     if (d.D == 64) return launch_td<float, 64>(L, st);
     if (d.D == 128) return launch_td<float, 128>(L, st);

@@ -112,6 +112,8 @@ struct GatherLaunch {
   void* Kbuf;
   void* Vbuf;
   int64_t buf_cap;
+  int32_t skip_front = 0, skip_back = 0;  // list entries left out at the two ends
+  int32_t* count_out = nullptr;           // receives count - skip_front - skip_back (>= 0) per list
 };
 tb_status launch_gather(const GatherLaunch& a, hipStream_t st);
 int attn_tile_rows_per_wg(int dtype, int D);

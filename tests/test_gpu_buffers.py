@@ -91,3 +91,85 @@ def test_buffered_interval_matches_fused_interval(oracle):
         o2, l2 = buffered.step(t, cfg.N + t, q, qi)
         torch.cuda.synchronize()
         assert torch.equal(o1, o2) and torch.equal(l1, l2), f"step {t}"
+
+
+def test_gather_important_skips_sink_and_window_entries(oracle):
+    say("migration of the middle of a list (sink and window entries left out)")
+    B, Hq, Hkv, D, N, cap = 2, 4, 2, 128, 900, 200
+    g = torch.Generator().manual_seed(5)
+    K = torch.randn((B, Hkv, N, D), generator=g).to(torch.bfloat16).to(DEV)
+    V = torch.randn((B, Hkv, N, D), generator=g).to(torch.bfloat16).to(DEV)
+    idx, cnt = make_lists(B, Hq, N, cap, 6)
+    cnt[1, 0] = 7  # shorter than what is skipped: nothing is migrated
+    d = tb.make_desc(N, Hq, K=K, V=V)
+    for front, back in ((0, 0), (5, 9), (16, 0), (0, 33)):
+        Kbuf = torch.full((B, Hq, cap, D), 7.0, dtype=torch.bfloat16, device=DEV)
+        Vbuf = torch.full_like(Kbuf, 7.0)
+        n_out = torch.full((B, Hq), -3, dtype=torch.int32, device=DEV)
+        tb.tb_gather_important(d, K, V, idx, cnt, cap, front, back, Kbuf, Vbuf, n_out)
+        torch.cuda.synchronize()
+        want_cnt = np.maximum(np_of(cnt) - front - back, 0)
+        assert np.array_equal(np_of(n_out), want_cnt)
+        shifted = np.zeros_like(np_of(idx))
+        shifted[..., : cap - front] = np_of(idx)[..., front:]
+        rK, rV = oracle.gather_kv(np_of(K), np_of(V), shifted, want_cnt, cap)
+        mask = (np.arange(cap)[None, None, :] < want_cnt[..., None])[..., None]
+        seven = np_of(torch.full((1,), 7.0, dtype=torch.bfloat16))[0]
+        assert np.array_equal(np.where(mask, np_of(Kbuf), 0), rK) and np.array_equal(np.where(mask, np_of(Vbuf), 0), rV)
+        assert np.all(np.where(mask, seven, np_of(Kbuf)) == seven), "rows beyond the count stay untouched"
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_ring_layout_interval_loop(oracle, mode):
+    """Sink Buffer + Local Window ring + Important Buffer with the projection deferred to the
+    wraps of the ring (Sec. 3.3 "Inference Setup"), over more than two wraps, every step against
+    the oracle's driver in ring mode: selection, widened list and migrated row counts bit-exact,
+    attention to the bar.  The projected-key cache starts with the post-prefill rows only."""
+    ring, sink = 8, 16
+    cfg = workloads.C4.scaled(name="C4_small_ring", B=2, N=4096, k=256, steps=21, P=4, heavy_per_kv_head=8)
+    say(f"ring layout: ring={ring} sink={sink} P={cfg.P} steps={cfg.steps} neighbour rule {mode}")
+    data = workloads.make_layer(cfg, device=DEV)
+    K, V, W = data["K"], data["V"], data["W"]
+    B, Hq, Hkv, N0, D = cfg.B, cfg.Hq, cfg.Hkv, cfg.N, cfg.D
+    Kimp = torch.zeros((B, Hkv, K.shape[2], cfg.Dimp), dtype=K.dtype, device=DEV)
+    tb.tb_project_keys(tb.make_desc(N0, Hq, K=K, V=V, Kimp=Kimp), K, W, Kimp, 0, N0)  # post-prefill state
+    dec = interval.RingLayoutDecoder(K, V, W, Kimp, Hq, cfg.k, cfg.P, cfg.radius, ring, sink=sink,
+                                     sm_scale=cfg.sm_scale, mode=mode)
+    recs = []
+    for t in range(cfg.steps):
+        out, lse = dec.step(t, N0 + t, data["q"][t].contiguous(), data["q_imp"][t].contiguous())
+        pred = t % cfg.P == 0
+        recs.append((out.clone(), lse.clone(), dec.imp_cnt.clone(),
+                     dec.idx.clone() if pred else None, dec.cnt.clone() if pred else None,
+                     dec.exp_idx.clone() if pred else None, dec.exp_cnt.clone() if pred else None,
+                     dec.scores[:, :, : N0 + t].clone() if pred else None))
+    torch.cuda.synchronize()
+    assert dec.projections == (cfg.steps - 1) // ring and dec.projections >= 2
+    # the deferred batches left the same projected keys as one projection of the whole cache
+    # (rows past the last wrap are still unprojected)
+    upto = N0 + dec.projections * ring
+    ref_kimp = oracle.project_keys(np_of(K)[:, :, :upto], np_of(W), cfg.dtype)
+    assert np.mean(np_of(Kimp)[:, :, :upto] == ref_kimp) > 0.99 and not np_of(Kimp)[:, :, upto:].any()
+    Kn, Vn, Kin = np_of(K), np_of(V), np_of(Kimp)
+    drv = oracle.IntervalDriver(cfg.dtype, cfg.k, cfg.P, cfg.radius, sink=sink, sm_scale=cfg.sm_scale, mode=mode,
+                                ring=ring)
+    for t in range(cfg.steps):
+        N_t, W_t = N0 + t, min(ring, t)
+        u_idx, u_cnt = drv.lists(t, N_t, np_of(data["q_imp"][t]), Kin)
+        if t % cfg.P == 0:
+            g_idx, g_cnt = np_of(recs[t][3]), np_of(recs[t][4])
+            s_idx, s_cnt = oracle.select_topk(np_of(recs[t][7]), cfg.k, sink, W_t)
+            assert np.array_equal(s_cnt, g_cnt) and np.array_equal(s_idx, g_idx[..., : s_idx.shape[-1]])
+            e_idx, e_cnt = oracle.expand_neighbors(g_idx, g_cnt, N_t, cfg.radius, cap_out=recs[t][5].shape[-1], mode=mode)
+            assert np.array_equal(np_of(recs[t][6]), e_cnt)
+            mask = np.arange(e_idx.shape[-1])[None, None] < e_cnt[..., None]
+            assert np.array_equal(np.where(mask, np_of(recs[t][5]), -1), np.where(mask, e_idx, -1))
+            drv.exp_idx, drv.exp_cnt = e_idx, e_cnt  # continue the oracle from the GPU's selection
+            u_idx, u_cnt = e_idx, e_cnt
+            W_p = W_t
+        else:
+            assert np.array_equal(u_cnt, drv.exp_cnt - W_p + W_t)
+        assert np.array_equal(np_of(recs[t][2]), drv.exp_cnt - sink - W_p), f"step {t}: rows in the Important Buffer"
+        ro, rl = oracle.sparse_decode_attn(np_of(data["q"][t]), Kn[:, :, :N_t], Vn[:, :, :N_t], u_idx, u_cnt, cfg.dtype,
+                                           cfg.sm_scale)
+        assert_attention(np_of(recs[t][0]), ro, cfg.dtype, np_of(recs[t][1]), rl, what=f"step {t}")

@@ -584,6 +584,66 @@ def test_interval_driver_expand_on_predict(oracle):
             assert np.array_equal(ca, cc) and np.array_equal(oa, oc) and np.array_equal(la, lc)
 
 
+def test_interval_driver_ring_layout(oracle):
+    """Sec. 3.3 "Inference Setup" (Sink Buffer, Local Window ring, Important Buffer) as the
+    driver's ring mode.  Pins: with P = 1 every step is decode attention over the widened
+    selection made with the window that has filled so far (min(ring, t) tokens), computed here
+    from the separate calls; with P > 1 a reuse step attends over exactly the plain driver's set
+    minus the rows that have left the window since the prediction, and its length is
+    |widened list| - W_pred + W_t."""
+    rng = np.random.default_rng(33)
+    B, Hq, Hkv, N0, D, d, k, steps, S, W = 1, 4, 2, 140, 16, 8, 9, 14, 3, 5
+    Ncap = N0 + steps
+    K = rng.standard_normal((B, Hkv, Ncap, D)).astype(np.float32)
+    V = rng.standard_normal((B, Hkv, Ncap, D)).astype(np.float32)
+    Wm = (rng.standard_normal((1, D, d)) / 4).astype(np.float32)
+    Kimp = oracle.project_keys(K, Wm, "f32")
+    qs = rng.standard_normal((steps, B, Hq, D)).astype(np.float32)
+    qis = rng.standard_normal((steps, B, Hq, d)).astype(np.float32)
+    # P = 1: per-step path with the window that has filled so far, attention over the widened list
+    drv = oracle.IntervalDriver("f32", k, P=1, radius=1, sink=S, sm_scale=0.25, ring=W)
+    for t in range(steps):
+        N_t = N0 + t
+        out, lse, idx, cnt = drv.step(t, N_t, qs[t], qis[t], K, V, Kimp)
+        s = oracle.score(qis[t], Kimp[:, :, :N_t], "f32", 1.0)
+        sel, scnt = oracle.select_topk(s, k, S, min(W, t))
+        assert np.all(scnt == S + k + min(W, t))
+        eidx, ecnt = oracle.expand_neighbors(sel, scnt, N_t, 1)
+        out2, lse2 = oracle.sparse_decode_attn(qs[t], K[:, :, :N_t], V[:, :, :N_t], eidx, ecnt, "f32", 0.25)
+        assert np.array_equal(cnt, ecnt) and np.array_equal(out, out2) and np.array_equal(lse, lse2)
+        # the unprojected tail is never looked at: garbage projected keys there change nothing
+        Kbad = Kimp.copy()
+        Kbad[:, :, N_t - min(W, t):] = 1e30
+        drv2 = oracle.IntervalDriver("f32", k, P=1, radius=1, sink=S, sm_scale=0.25, ring=W)
+        drv2.N0 = N0
+        o3, _, _, c3 = drv2.step(0, N_t, qs[t], qis[t], K, V, Kbad)
+        assert np.array_equal(o3, out) and np.array_equal(c3, cnt)
+    # P = 4 <= W: reuse steps against the plain driver that is given the same window at the
+    # prediction steps (fixed window W once the ring is full: compare from the first prediction
+    # step with a full ring on)
+    P = 4
+    ring = oracle.IntervalDriver("f32", k, P=P, radius=1, sink=S, sm_scale=0.25, ring=W)
+    plain = oracle.IntervalDriver("f32", k, P=P, radius=1, sink=S, window=W, sm_scale=0.25, expand_on_predict=True)
+    for t in range(steps):
+        N_t = N0 + t
+        ri, rc = ring.lists(t, N_t, qis[t], Kimp)
+        pi, pc = plain.lists(t, N_t, qis[t], Kimp)
+        W_t = min(W, t)
+        if t % P == 0:
+            N_p, W_p, e_cnt = N_t, W_t, ring.exp_cnt.copy()
+            assert np.array_equal(rc, e_cnt)
+            for h in range(Hq):  # sink first, the window last
+                assert np.array_equal(ri[0, h, :S], np.arange(S)) and np.array_equal(ri[0, h, rc[0, h] - W_t: rc[0, h]], np.arange(N_t - W_t, N_t))
+        else:
+            assert np.array_equal(rc, e_cnt - W_p + W_t)
+        if t >= 2 * P:  # both drivers predicted with a full ring
+            for h in range(Hq):
+                a = set(ri[0, h, : rc[0, h]].tolist())
+                b = set(pi[0, h, : pc[0, h]].tolist())
+                assert a == b - set(range(N_p - W_p, N_t - W_t)), (t, h)
+                assert len(a) == rc[0, h], "no position twice"
+
+
 # --------------------------------------------------------------------------- buffer migration
 
 def test_gather_kv_rows_are_copies_in_list_order(oracle):
