@@ -79,7 +79,7 @@ tb_status tb_score(const tb_cache_desc* desc, const void* q_imp, const void* Kim
  *   idx = [0,lo) ++ ascending(kept) ++ [hi,N),   count = lo + kk + (N - hi).
  * idx: int32 [B][Hq][idx_cap], idx_cap >= lo + kk + (N - hi); entries beyond count are left
  * untouched.  count: int32 [B][Hq].  ws / ws_bytes are optional (NULL / 0 is fine): the selection
- * keeps its scratch on chip, except that long rows (N >= 131072 with a budget of at most an
+ * keeps its scratch on chip, except that long rows (N > 65536 with a budget of at most an
  * eighth of the candidates) are cut into pieces that are filtered by several compute units and
  * then combined, which needs tb_workspace_bytes(TB_OP_SELECT, desc, sink + k + window) bytes;
  * with less, one workgroup selects the whole row (same result, slower). */

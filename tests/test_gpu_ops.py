@@ -147,6 +147,8 @@ def test_select_sizes_random_scores(oracle, N):
 
 
 @pytest.mark.parametrize("N,ks", [
+    (65537, (1, 4096, 8192)),            # one score more than a workgroup holds in registers
+    (70001, (4096, 8000, 35000)),        # a short last piece
     (131072, (4096, 13000, 65536)),      # streamed rows: the bracket's keys fit the LDS list
     (300001, (1, 4096, 30000, 150000)),  # ... and overflow it for the larger budgets
     (1 << 20, (4096, 104857)),           # longest supported row
