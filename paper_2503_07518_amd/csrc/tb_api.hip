@@ -1,5 +1,6 @@
 // C ABI of libtokenbutler: argument validation on the host, workspace layout, launch plans.
 // Every entry point only enqueues kernels on the caller's stream.
+#include <cmath>
 #include <mutex>
 
 #include "tb_internal.h"
@@ -49,27 +50,39 @@ bool attn_shared_list_grouped(const tb_cache_desc* d) {
 }
 
 SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk) {
-  SelectPlan p{1, 0, 0, 2};
+  SelectPlan p{1, 0, 0, 2, 16, 16};
   // worth it when the budget is a small share of the candidates (the kept keys are then a small
   // share of the row as well) and the row is longer than the 65536 scores one workgroup holds in
   // registers (beyond that it would stream the row again in every phase: 44 against 27 us just
   // past 65536); up to 65536 scores two launches cost more than the one-workgroup selection
   if (units <= 0 || kk <= 0 || N <= 65536 || kk * 8 > candidates) return p;
-  int64_t len = 32768;
-  if (units * ((N + len - 1) / len) > 512) len = 65536;   // at most two rounds of workgroups on 256 compute units
-  // few rows (a head-less selection has one per batch element): more, shorter pieces, so that
-  // more compute units take part
-  if (units * ((N + len - 1) / len) < 64) len = (((N + 15) / 16 + 4095) / 4096 * 4096 > 8192) ? ((N + 15) / 16 + 4095) / 4096 * 4096 : 8192;
-  if ((N + len - 1) / len > 16) len = ((N + 15) / 16 + 4095) / 4096 * 4096;
-  if (len > 65536) return p;                              // a piece has to fit the registers of its workgroup
+  int waves = 8, tiles = 8;
+  auto len_of = [&]() { return static_cast<int64_t>(waves) * 256 * tiles; };
+  // few rows (a head-less selection has one per batch element): shorter pieces, so that more
+  // compute units take part
+  while (units * ((N + len_of() - 1) / len_of()) < 256 && (tiles > 2 || waves > 4)) {
+    if (tiles > 2) tiles /= 2; else waves /= 2;
+  }
+  while ((N + len_of() - 1) / len_of() > 256 && tiles < 16) tiles *= 2;  // the table of stage B has 256 entries
+  const int64_t len = len_of();
   const int64_t pieces = (N + len - 1) / len;
-  if (pieces < 2) return p;
+  if (pieces < 2 || pieces > 256) return p;
   p.pieces = static_cast<int>(pieces);
   p.piece_len = len;
+  p.piece_waves = waves;
+  p.piece_tiles = tiles;
   const int64_t cap = 2 * kk + 4096;                      // the budget, the bracket's slack, a coarse top bin
   p.cap = ((cap < len ? cap : len) + 3) / 4 * 4;
-  const int64_t tiles = (pieces * p.cap + 4095) / 4096;   // at most: the pieces' capacity
-  p.stage_b_tiles = tiles <= 2 ? 2 : (tiles <= 4 ? 4 : (tiles <= 8 ? 8 : 16));
+  // what the pieces keep together, give or take: the share of the row above the lower end of the
+  // bracket (the rank of the threshold in a sample of 4 keys per thread plus twice the bracket's
+  // slack: the lower end lies one slack below the expected rank, and its 12-bit bin reaches further
+  // down), every piece padded to a multiple of 4
+  const double n_s = 4.0 * 64 * waves, frac = static_cast<double>(kk) / static_cast<double>(candidates);
+  const double ks = frac * n_s, slack = 6.0 * sqrt(ks * (1.0 - frac)) + 4.0;
+  double kept = (ks + 2.0 * slack) / n_s * static_cast<double>(candidates) + 3.0 * static_cast<double>(pieces);
+  if (kept > static_cast<double>(pieces * p.cap)) kept = static_cast<double>(pieces * p.cap);
+  const int64_t t4k = (static_cast<int64_t>(kept) + 4095) / 4096;
+  p.stage_b_tiles = t4k <= 2 ? 2 : (t4k <= 4 ? 4 : (t4k <= 8 ? 8 : 16));
   return p;
 }
 

@@ -93,6 +93,10 @@ __device__ inline uint32_t score_key(float s) {
 }
 
 __device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }
+// Index of the wave inside its workgroup, as a value the compiler knows to be the same in every
+// lane: what is derived from it (the wave's span of a row, its LDS region, branches on them)
+// stays in scalar registers and scalar branches.
+__device__ inline int wave_id() { return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / kWave); }
 
 // Inclusive prefix sum across the 64 lanes of a wave (generic: LDS-crossbar shuffles).
 template <typename T>

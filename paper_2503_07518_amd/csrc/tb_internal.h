@@ -56,6 +56,8 @@ struct SelectPlan {
   int64_t piece_len;  // scores per piece
   int64_t cap;        // kept keys a piece has room for (a multiple of 4)
   int stage_b_tiles;  // 4096-key tiles of kept keys that stage B holds in registers: 2, 4, 8 or 16
+  int piece_waves;    // waves of a stage-A workgroup: 4, 8 or 16
+  int piece_tiles;    // 256-key tiles that each of them keeps in registers: 2, 4, 8 or 16
 };
 SelectPlan select_plan(int64_t units, int64_t candidates, int64_t N, int64_t kk);
 // kept positions int32 and keys uint32, [units][pieces][cap] each, then 4 words of header per piece

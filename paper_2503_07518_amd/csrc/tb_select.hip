@@ -58,6 +58,7 @@ struct SelectArgs {
   int32_t pieces;
   int64_t piece_len;
   int64_t cap;
+  int64_t units;  // rows of the launch (stage A maps its workgroups to rows and pieces itself)
   int32_t* cand_idx;
   uint32_t* cand_key;
   uint32_t* piece_hdr;
@@ -103,7 +104,7 @@ __device__ inline uint32_t wave_entries_scan(const uint32_t* s_w, uint32_t& tota
   if (W > 4) incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 4, 0xF, 0xF, false);
   if (W > 8) incl += __builtin_amdgcn_update_dpp(0u, incl, kRowShr + 8, 0xF, 0xF, false);
   total = __builtin_amdgcn_readlane(incl, W - 1);
-  return __builtin_amdgcn_readlane(incl - v, threadIdx.x / kWave);
+  return __builtin_amdgcn_readlane(incl - v, wave_id());
 }
 
 // Result of a histogram walk, published in LDS for the whole workgroup.
@@ -139,7 +140,7 @@ __device__ inline Found find_bins(const uint32_t* s_hist, uint32_t extra, uint32
   constexpr int BL = BW / kWave;     // bins per lane
   static_assert(BL >= 4 && BL % 4 == 0, "whole 128-bit reads per lane");
   const int lane = lane_id();
-  const int wave = threadIdx.x / kWave;
+  const int wave = wave_id();
   const uint32_t extra_incl = wave_incl_scan_u32(extra);
   if (lane == kWave - 1) s_extra[wave] = extra_incl;
   __syncthreads();  // the histogram and s_extra are complete
@@ -203,9 +204,10 @@ template <int W>
 __device__ inline void sample_bracket(const uint32_t* s_hist, uint32_t n_valid, uint32_t* s_extra, uint32_t* s_wsum,
                                       Found* s_found, int kk, int64_t n_cand, uint32_t& b_lo, uint32_t& b_hi) {
   const Found fb = find_bins<W>(s_hist, n_valid, s_extra, s_wsum, s_found, [&](uint32_t n_s, uint32_t& na, uint32_t& nb) {
-    const float frac = static_cast<float>(kk) / static_cast<float>(n_cand);
+    // (hardware reciprocal and square root: approximate, which is all a heuristic needs)
+    const float frac = static_cast<float>(kk) * __builtin_amdgcn_rcpf(static_cast<float>(n_cand));
     const float ks_f = frac * static_cast<float>(n_s);
-    const float margin = 6.0f * sqrtf(ks_f * (1.0f - frac)) + 4.0f;
+    const float margin = 6.0f * __builtin_amdgcn_sqrtf(ks_f * (1.0f - frac)) + 4.0f;
     const float hi_f = ks_f - margin, lo_f = ks_f + margin;
     na = hi_f < 1.0f ? 0u : static_cast<uint32_t>(hi_f);  // 0: no bin is safely above T
     nb = lo_f >= static_cast<float>(n_s) ? n_s + 1u : static_cast<uint32_t>(lo_f) + 1u;
@@ -279,7 +281,7 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
+  const int wave = wave_id();
   const int kk = a.kk;
   // stage B: the row is the concatenation of the pieces' kept keys, every piece padded to a
   // multiple of 4; every key of it is a candidate
@@ -693,6 +695,93 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
   write_fixed_ranges();
 }
 
+// ---- moving the scores at or above a bound into a list, with few instructions per score ----------
+// A SIMD issues about one instruction in four cycles whatever its kind, so a pass over a row
+// costs what it spends per score.  This pass spends one floating-point compare per score (the
+// lane masks of a wave tile's four compares stay in scalar registers), eight mask-count
+// instructions per tile for the number of entries in lower lanes, and per score one store of
+// (score bits, position) -- to the next free slot of the wave's region in LDS, or to a spare
+// slot of the lane when the score is below the bound, instead of a branch.  The regions hold
+// their entries in position order.
+template <int W, int NT, int CAP_PER_TILE>
+struct RegionLds {
+  static constexpr int kCap = NT * CAP_PER_TILE;  // entries per wave (a tile has 256 scores)
+  // The waves' regions one after the other, then one spare slot per lane.  pos mirrors key at a
+  // fixed distance, so that one instruction writes both.  A wave with more entries than its
+  // region holds runs on into what follows -- the caller then discards the list, but the stores
+  // must stay inside the arrays: the last wave's can reach NT * 256 - kCap entries past its
+  // region, which `spill` covers.
+  uint32_t key[W * kCap + kWave];  // raw score bits
+  int32_t pos[W * kCap + kWave];   // position in the row
+  uint32_t spill[NT * kWaveTile - kCap];
+  uint32_t cnt[W];
+};
+
+// Smallest score whose key is `key` (a key that a real score produces).
+__device__ inline float score_of_key(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
+}
+constexpr uint32_t kKeyOfMinusInf = 0x007FFFFFu;
+
+__device__ inline uint32_t mbcnt64(unsigned long long m, uint32_t acc) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), acc));
+}
+__device__ inline uint32_t popc64(unsigned long long m) { return static_cast<uint32_t>(__popcll(m)); }
+
+// Appends the candidates (positions in [lo, hi)) among the wave's NT tiles `raw` -- tile j holds
+// the positions pos0 + 256 j + 4 lane .. + 3 -- whose score is at least f_lo (`all`: every
+// candidate, NaN included) to the wave's region, and returns their number, the same in every
+// lane; beyond RegionLds::kCap the region has overflowed.
+template <int W, int NT, int CPT>
+__device__ __forceinline__ uint32_t append_at_least(const float4 (&raw)[NT], const int pos0, const int lo, const int hi,
+                                                    const float f_lo, const bool all, RegionLds<W, NT, CPT>& rl, const int wave,
+                                                    const int lane) {
+  using R = RegionLds<W, NT, CPT>;
+  constexpr int kCap = R::kCap;
+  constexpr int kPosOff = static_cast<int>(sizeof(rl.key) / 4);  // pos[i] is key[i + kPosOff]
+  static_assert(offsetof(R, pos) == sizeof(rl.key), "pos follows key");
+  uint32_t* const lkey = rl.key + wave * kCap;
+  uint32_t* const spare = rl.key + W * kCap + lane;
+  uint32_t run = 0;
+  auto append = [&](int j, bool t0, bool t1, bool t2, bool t3) {
+    const float v0 = raw[j].x, v1 = raw[j].y, v2 = raw[j].z, v3 = raw[j].w;
+    const int p0 = pos0 + j * kWaveTile + lane * 4;
+    const unsigned long long m0 = __ballot(t0), m1 = __ballot(t1), m2 = __ballot(t2), m3 = __ballot(t3);
+    uint32_t* w = lkey + run + mbcnt64(m3, mbcnt64(m2, mbcnt64(m1, mbcnt64(m0, 0u))));  // after the entries of lower lanes and earlier tiles
+    uint32_t* d;
+    d = t0 ? w : spare;
+    d[0] = __float_as_uint(v0);
+    d[kPosOff] = static_cast<uint32_t>(p0);
+    w += t0 ? 1 : 0;
+    d = t1 ? w : spare;
+    d[0] = __float_as_uint(v1);
+    d[kPosOff] = static_cast<uint32_t>(p0 + 1);
+    w += t1 ? 1 : 0;
+    d = t2 ? w : spare;
+    d[0] = __float_as_uint(v2);
+    d[kPosOff] = static_cast<uint32_t>(p0 + 2);
+    w += t2 ? 1 : 0;
+    d = t3 ? w : spare;
+    d[0] = __float_as_uint(v3);
+    d[kPosOff] = static_cast<uint32_t>(p0 + 3);
+    run += popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);  // (scalar instructions)
+  };
+  if (pos0 >= lo && pos0 + NT * kWaveTile <= hi) {  // the usual case: every score of the wave's span is a candidate
+#pragma unroll
+    for (int j = 0; j < NT; ++j) append(j, all || raw[j].x >= f_lo, all || raw[j].y >= f_lo, all || raw[j].z >= f_lo, all || raw[j].w >= f_lo);
+  } else {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int n_t = pos0 + j * kWaveTile;
+      if (n_t >= hi || n_t + kWaveTile <= lo) continue;
+      const int p0 = n_t + lane * 4;
+      append(j, (all || raw[j].x >= f_lo) && p0 >= lo && p0 < hi, (all || raw[j].y >= f_lo) && p0 + 1 >= lo && p0 + 1 < hi,
+             (all || raw[j].z >= f_lo) && p0 + 2 >= lo && p0 + 2 < hi, (all || raw[j].w >= f_lo) && p0 + 3 >= lo && p0 + 3 < hi);
+    }
+  }
+  return run;
+}
+
 constexpr int kSelWaves = 16;  // one workgroup per row
 constexpr int kSelThreads = kSelWaves * kWave;
 
@@ -707,101 +796,143 @@ __global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void sel
   }
 }
 
-// ---- selection of a row by pieces, stage A.  The piece's keys are in registers (NT tiles per
+// ---- selection of a row by pieces, stage A.  The piece's scores are in registers (NT tiles per
 // wave).  Every piece of a row takes the same sample of the row's candidates (one 128-bit load
 // per thread at positions spread evenly over [lo, hi)) and so arrives at the same bracket as its
-// siblings.  The keys at or above the bracket's lower end are kept, in position order.
+// siblings.  The scores whose keys are at or above the bracket's lower end are kept, in position
+// order: collected per wave in LDS, then copied out behind the entries of the waves before.
+constexpr int kPieceCapPerTile = 56;  // a wave's region holds 22% of its span: several times what a piece keeps
 template <int W, int NT>
-__device__ __forceinline__ void piece_body(const SelectArgs& a, const int u, const int c, SelLds<W>& sl) {
+struct PieceLds {
+  uint32_t hist[kHistBins];
+  __attribute__((aligned(16))) Found found;
+  uint32_t part[W], wsum[W], wgt[W];
+  RegionLds<W, NT, kPieceCapPerTile> reg;
+};
+
+template <int W, int NT>
+__device__ __forceinline__ void piece_body(const SelectArgs& a, const int u, const int c, PieceLds<W, NT>& pl) {
   constexpr int kThreads = W * kWave;
-  uint32_t* s_hist = sl.hist[0];
+  constexpr int kCap = RegionLds<W, NT, kPieceCapPerTile>::kCap;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
+  const int wave = wave_id();
   const int64_t base = c * a.piece_len;
   int64_t n_c = a.N - base;
   n_c = n_c < 0 ? 0 : (n_c > a.piece_len ? a.piece_len : n_c);
-  int64_t lo_c = a.lo - base, hi_c = a.hi - base;  // the candidates of this piece, as positions inside it
-  lo_c = lo_c < 0 ? 0 : (lo_c > n_c ? n_c : lo_c);
-  hi_c = hi_c < lo_c ? lo_c : (hi_c > n_c ? n_c : hi_c);
   const float* row = a.scores + static_cast<int64_t>(u) * a.score_stride;
   const float* s = row + base;
-  const int64_t last4 = n_c > 0 ? ((n_c - 1) & ~int64_t{3}) : 0;
-  const int64_t wbase = static_cast<int64_t>(wave) * NT * kWaveTile + lane * 4;
+  const int last4 = n_c > 0 ? static_cast<int>((n_c - 1) & ~int64_t{3}) : 0;
+  const int wspan0 = wave * NT * kWaveTile;  // the wave's span, as positions inside the piece
   // the sample of the whole row: four adjacent scores at each of `kThreads` positions spread
   // evenly over the candidates
   const int64_t span = a.hi - a.lo;
   const int64_t sp = (a.lo + (tid * span) / kThreads) & ~int64_t{3};
   const int64_t row_last4 = (a.N - 1) & ~int64_t{3};
-  uint32_t keys[NT][4];
-  float4 sraw;
-  {
-    float4 raw[NT];
+  float4 raw[NT];
 #pragma unroll
-    for (int j = 0; j < NT; ++j) raw[j] = load_scores4(s, last4, wbase + j * kWaveTile);
-    sraw = load_scores4(row, row_last4, sp);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < NT; ++j)
-      keys_of4(raw[j], static_cast<int>(lo_c), static_cast<int>(hi_c), wbase + j * kWaveTile, keys[j]);
+  for (int j = 0; j < NT; ++j) {
+    const int n0 = wspan0 + j * kWaveTile + lane * 4;
+    raw[j] = *reinterpret_cast<const float4*>(s + (n0 < last4 ? n0 : last4));  // (past the piece's end: excluded by position below)
   }
+  const float4 sraw = load_scores4(row, row_last4, sp);
+  __builtin_amdgcn_sched_barrier(0);
 
-  for (int i = tid; i < kHistBins; i += kThreads) s_hist[i] = 0;
-  if (tid < kFoundWords) reinterpret_cast<uint32_t*>(&sl.found[0])[tid] = 0;
+  {
+    uint4* z = reinterpret_cast<uint4*>(pl.hist);
+    for (int i = tid; i < kHistBins / 4; i += kThreads) z[i] = make_uint4(0u, 0u, 0u, 0u);
+  }
+  if (tid < kFoundWords) reinterpret_cast<uint32_t*>(&pl.found)[tid] = 0;
   __syncthreads();
   uint32_t n_valid = 0;
   {
     uint32_t sk[4];
     keys_of4(sraw, a.lo, a.hi, sp, sk);  // (the four may straddle an end of the candidate range)
-    // all four enter the histogram (4096 keys): a piece does little else, and a narrower bracket
-    // means fewer kept keys to store and to select among
+    // all four enter the histogram: a narrower bracket means fewer kept keys to store and to
+    // select among
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (sk[i]) {
-        atomicAdd(&s_hist[sk[i] >> kTopShift], 1u);
+        atomicAdd(&pl.hist[sk[i] >> kTopShift], 1u);
         ++n_valid;
       }
     }
   }
   uint32_t b_lo, b_hi;
-  sample_bracket<W>(s_hist, n_valid, sl.part[0], sl.wsum, &sl.found[0], a.kk, span, b_lo, b_hi);
+  sample_bracket<W>(pl.hist, n_valid, pl.part, pl.wsum, &pl.found, a.kk, span, b_lo, b_hi);
   const uint32_t t_lo = b_lo << kTopShift;  // keys from here up are kept
+  // a score is kept when it is at least f_lo; a lower end at or below the key of -inf keeps
+  // every candidate (NaN, whose key is that of -inf, included)
+  const bool all = t_lo <= kKeyOfMinusInf;
+  const float f_lo = all ? 0.f : score_of_key(t_lo);
 
-  // ordered compaction of the piece's kept keys (prefix sums as in the selection itself)
-  uint32_t pre[NT];
-  uint32_t run = 0;
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    uint32_t cnt = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) cnt += keys[j][e] >= t_lo ? 1u : 0u;
-    const uint32_t incl = wave_incl_scan_u32(cnt);
-    pre[j] = run + incl - cnt;
-    run += __builtin_amdgcn_readlane(incl, kWave - 1);
-  }
-  if (lane == 0) sl.wgt[wave] = run;
+  // positions are those of the whole row; candidates past the piece's end do not exist (the
+  // last piece ends with the row, and hi <= N)
+  const int pos0 = static_cast<int>(base) + wspan0;
+  const uint32_t run = append_at_least<W, NT>(raw, pos0, a.lo, a.hi, f_lo, all, pl.reg, wave, lane);
+  if (lane == 0) pl.reg.cnt[wave] = run;
   __syncthreads();
   uint32_t total;
-  const uint32_t wave_base = wave_entries_scan<W>(sl.wgt, total);
+  const uint32_t wave_base = wave_entries_scan<W>(pl.reg.cnt, total);
+  const int l16 = lane & 15;
+  const bool overflowed = __ballot(l16 < W && pl.reg.cnt[l16 < W ? l16 : 0] > static_cast<uint32_t>(kCap)) != 0ull;
   int32_t* out_idx = a.cand_idx + (static_cast<int64_t>(u) * a.pieces + c) * a.cap;
   uint32_t* out_key = a.cand_key + (static_cast<int64_t>(u) * a.pieces + c) * a.cap;
-  if (tid < 3) {
-    uint32_t* hdr = a.piece_hdr + (static_cast<int64_t>(u) * a.pieces + c) * 4;
-    hdr[tid] = tid == 0 ? total : (tid == 1 ? b_lo : b_hi);
+  uint32_t* hdr = a.piece_hdr + (static_cast<int64_t>(u) * a.pieces + c) * 4;
+  if (!overflowed) {
+    if (tid < 3) hdr[tid] = tid == 0 ? total : (tid == 1 ? b_lo : b_hi);
+    const uint32_t* lkey = pl.reg.key + wave * kCap;
+    const int32_t* lpos = pl.reg.pos + wave * kCap;
+    for (uint32_t e = lane; e < run; e += kWave) {
+      const uint32_t at = wave_base + e;
+      if (at < static_cast<uint32_t>(a.cap)) {
+        out_idx[at] = lpos[e];
+        out_key[at] = score_key(__uint_as_float(lkey[e]));
+      }
+    }
+    return;
   }
+
+  // A wave of this piece holds more kept scores than its region (a dense cluster of large
+  // scores): the same result from the registers, by prefix sums over the keys.
+  int lo_c = static_cast<int>(a.lo - base < 0 ? 0 : (a.lo - base > n_c ? n_c : a.lo - base));
+  int hi_c = static_cast<int>(a.hi - base < lo_c ? lo_c : (a.hi - base > n_c ? n_c : a.hi - base));
+  __syncthreads();  // every wave has read the counts
+  uint32_t run2 = 0;
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
-    uint32_t pos = wave_base + pre[j];
+    uint32_t k4[4];
+    keys_of4(raw[j], lo_c, hi_c, wspan0 + j * kWaveTile + lane * 4, k4);
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) cnt += k4[e] >= t_lo ? 1u : 0u;
+    run2 += __builtin_amdgcn_readlane(wave_incl_scan_u32(cnt), kWave - 1);
+  }
+  if (lane == 0) pl.wgt[wave] = run2;
+  __syncthreads();
+  uint32_t total2;
+  uint32_t at = wave_entries_scan<W>(pl.wgt, total2);  // kept keys of the waves and tiles before
+  if (tid < 3) hdr[tid] = tid == 0 ? total2 : (tid == 1 ? b_lo : b_hi);
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    uint32_t k4[4];
+    keys_of4(raw[j], lo_c, hi_c, wspan0 + j * kWaveTile + lane * 4, k4);
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) cnt += k4[e] >= t_lo ? 1u : 0u;
+    const uint32_t incl = wave_incl_scan_u32(cnt);
+    uint32_t pos = at + incl - cnt;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      if (keys[j][e] >= t_lo) {
+      if (k4[e] >= t_lo) {
         if (pos < static_cast<uint32_t>(a.cap)) {
-          out_idx[pos] = static_cast<int32_t>(base + wbase + j * kWaveTile + e);
-          out_key[pos] = keys[j][e];
+          out_idx[pos] = static_cast<int32_t>(base) + wspan0 + j * kWaveTile + lane * 4 + e;
+          out_key[pos] = k4[e];
         }
         ++pos;
       }
     }
+    at += __builtin_amdgcn_readlane(incl, kWave - 1);
   }
 }
 
@@ -844,10 +975,30 @@ __global__ __launch_bounds__(kSelThreads, 4) void stage_b_kernel(SelectArgs a) {
   }
 }
 
-template <int NT>
-__global__ __launch_bounds__(kSelThreads, (NT >= 1 && NT <= 4) ? 8 : 4) void prefilter_kernel(SelectArgs a) {
-  __shared__ SelLds<kSelWaves> sl;
-  piece_body<kSelWaves, NT>(a, blockIdx.x / a.pieces, blockIdx.x % a.pieces, sl);
+// Stage A.  All pieces of a row run on one XCD (workgroups go to the eight XCDs round-robin by
+// their linear index), close together in time: the sample of the row that every piece takes is
+// then served by that XCD's L2, out of the lines that the row's pieces fetch anyway.
+template <int W, int NT>
+__global__ __launch_bounds__(W * kWave) void prefilter_kernel(SelectArgs a) {
+  __shared__ PieceLds<W, NT> sl;
+  const int64_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int64_t u = (slot / a.pieces) * 8 + xcd;
+  if (u >= a.units) return;  // (the launch is padded to a multiple of eight rows)
+  piece_body<W, NT>(a, static_cast<int>(u), static_cast<int>(slot % a.pieces), sl);
+}
+
+template <int W>
+tb_status launch_prefilter_w(const SelectArgs& a, int tiles, dim3 grid, hipStream_t st) {
+  const dim3 block(W * kWave);
+  if (tiles <= 2)
+    hipLaunchKernelGGL((prefilter_kernel<W, 2>), grid, block, 0, st, a);
+  else if (tiles <= 4)
+    hipLaunchKernelGGL((prefilter_kernel<W, 4>), grid, block, 0, st, a);
+  else if (tiles <= 8)
+    hipLaunchKernelGGL((prefilter_kernel<W, 8>), grid, block, 0, st, a);
+  else
+    hipLaunchKernelGGL((prefilter_kernel<W, 16>), grid, block, 0, st, a);
+  return hip_status(hipGetLastError());
 }
 
 tb_status launch_whole(const SelectArgs& a, int64_t units, hipStream_t st) {
@@ -887,6 +1038,7 @@ tb_status launch_stage_b(const SelectLaunch& L, const SelectPlan& plan, hipStrea
   a.pieces = plan.pieces;
   a.piece_len = plan.piece_len;
   a.cap = plan.cap;
+  a.units = L.units;
   a.cand_idx = static_cast<int32_t*>(L.scratch);
   a.cand_key = reinterpret_cast<uint32_t*>(a.cand_idx + L.units * per_unit);
   a.piece_hdr = a.cand_key + L.units * per_unit;
@@ -921,6 +1073,7 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   a.pieces = 1;
   a.piece_len = 0;
   a.cap = 0;
+  a.units = L.units;
   a.cand_idx = nullptr;
   a.cand_key = nullptr;
   a.piece_hdr = nullptr;
@@ -936,19 +1089,16 @@ tb_status launch_select(const SelectLaunch& L, hipStream_t st) {
   a.cand_idx = static_cast<int32_t*>(L.scratch);
   a.cand_key = reinterpret_cast<uint32_t*>(a.cand_idx + L.units * per_unit);
   a.piece_hdr = a.cand_key + L.units * per_unit;
-  const dim3 grid(static_cast<unsigned>(L.units * plan.pieces)), block(kSelThreads);
-  const int tiles = static_cast<int>((plan.piece_len + kSelWaves * kWaveTile - 1) / (kSelWaves * kWaveTile));
-  if (tiles <= 1)
-    hipLaunchKernelGGL(prefilter_kernel<1>, grid, block, 0, st, a);
-  else if (tiles <= 2)
-    hipLaunchKernelGGL(prefilter_kernel<2>, grid, block, 0, st, a);
-  else if (tiles <= 4)
-    hipLaunchKernelGGL(prefilter_kernel<4>, grid, block, 0, st, a);
-  else if (tiles <= 8)
-    hipLaunchKernelGGL(prefilter_kernel<8>, grid, block, 0, st, a);
+  a.units = L.units;
+  const dim3 grid(static_cast<unsigned>((L.units + 7) / 8 * 8 * plan.pieces));
+  tb_status rc;
+  if (plan.piece_waves == 4)
+    rc = launch_prefilter_w<4>(a, plan.piece_tiles, grid, st);
+  else if (plan.piece_waves == 8)
+    rc = launch_prefilter_w<8>(a, plan.piece_tiles, grid, st);
   else
-    hipLaunchKernelGGL(prefilter_kernel<16>, grid, block, 0, st, a);
-  if (hipGetLastError() != hipSuccess) return TB_ERR_HIP;
+    rc = launch_prefilter_w<16>(a, plan.piece_tiles, grid, st);
+  if (rc != TB_OK) return rc;
   return launch_stage_b(L, plan, st);
 }
 
