@@ -107,6 +107,12 @@ __device__ inline uint32_t wave_entries_scan(const uint32_t* s_w, uint32_t& tota
   return __builtin_amdgcn_readlane(incl - v, wave_id());
 }
 
+// Number of set bits of a lane mask below this lane, added to acc; number of set bits.
+__device__ inline uint32_t mbcnt64(unsigned long long m, uint32_t acc) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), acc));
+}
+__device__ inline uint32_t popc64(unsigned long long m) { return static_cast<uint32_t>(__popcll(m)); }
+
 // Result of a histogram walk, published in LDS for the whole workgroup.
 struct Found {
   uint32_t bin_a, above_a;  // bin in which the running count (from the top bin down) reaches target a, count above it
@@ -600,6 +606,38 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int u, co
       }
       return cnt;
     };
+    if constexpr (!TIES && NT > 0) {
+      // Keys in registers and no tie to cut: the lane masks of the compares (scalar registers)
+      // give the counts (bit counts, scalar) and the positions (mask counts below the lane).
+      uint32_t run = 0;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        if (kStageB && j >= tpw) break;
+        run += popc64(__ballot(keys[j][0] > T)) + popc64(__ballot(keys[j][1] > T)) + popc64(__ballot(keys[j][2] > T)) +
+               popc64(__ballot(keys[j][3] > T));
+      }
+      if (lane == 0) s_wgt[wave] = run;
+      __syncthreads();
+      uint32_t unused;
+      uint32_t at = wave_entries_scan<W>(s_wgt, unused);  // kept keys of the waves and tiles before
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        if (kStageB && j >= tpw) break;
+        const bool t0 = keys[j][0] > T, t1 = keys[j][1] > T, t2 = keys[j][2] > T, t3 = keys[j][3] > T;
+        const unsigned long long m0 = __ballot(t0), m1 = __ballot(t1), m2 = __ballot(t2), m3 = __ballot(t3);
+        const uint32_t tot = popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);
+        if (at + tot <= static_cast<uint32_t>(kk)) {  // (always, when the counts above add up)
+          int32_t* o = sel_out + at + mbcnt64(m3, mbcnt64(m2, mbcnt64(m1, mbcnt64(m0, 0u))));
+          const int32_t nn = static_cast<int32_t>(wbase) + j * kWaveTile;
+          if (t0) *o++ = kStageB ? cidx[(kStageB && NT > 0) ? j : 0][0] : nn;
+          if (t1) *o++ = kStageB ? cidx[(kStageB && NT > 0) ? j : 0][1] : nn + 1;
+          if (t2) *o++ = kStageB ? cidx[(kStageB && NT > 0) ? j : 0][2] : nn + 2;
+          if (t3) *o = kStageB ? cidx[(kStageB && NT > 0) ? j : 0][3] : nn + 3;
+        }
+        at += tot;
+      }
+      return;
+    }
     constexpr bool kKeepPre = NT > 0 && NT <= 8;  // keep the in-tile prefixes when registers allow
     uint32_t pre[kKeepPre ? NT : 1];
     if (kStream && list_ok) {
@@ -723,10 +761,6 @@ __device__ inline float score_of_key(uint32_t key) {
 }
 constexpr uint32_t kKeyOfMinusInf = 0x007FFFFFu;
 
-__device__ inline uint32_t mbcnt64(unsigned long long m, uint32_t acc) {
-  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), acc));
-}
-__device__ inline uint32_t popc64(unsigned long long m) { return static_cast<uint32_t>(__popcll(m)); }
 
 // Appends the candidates (positions in [lo, hi)) among the wave's NT tiles `raw` -- tile j holds
 // the positions pos0 + 256 j + 4 lane .. + 3 -- whose score is at least f_lo (`all`: every

@@ -176,20 +176,52 @@ def test_select_streamed_rows(oracle, N, ks):
         check_select(oracle, tied, N, ks[-1], 3, 5, ws=ws)
         check_select(oracle, asc, N, ks[0], 0, 0, ws=ws)
         check_select(oracle, -asc, N, ks[0], 2, 0, ws=ws)
-    # rows whose sample misleads the first stage (it looks at 256 clusters of 16 adjacent scores):
-    # huge values exactly there -> the pieces keep fewer keys than the budget; hugely negative ones
-    # exactly there -> the pieces keep far more than they have room for.  Both must
-    # end in the same lists (the second stage then selects on the whole row).
-    span = N
-    cluster = torch.tensor([((c * span) // 256) & ~15 for c in range(256)])
-    pos = (cluster[:, None] + torch.arange(16)[None, :]).reshape(-1)
-    pos = pos[pos < N]
+    # rows whose sample misleads the first stage: huge values exactly where it looks -> the pieces
+    # keep fewer keys than the budget; hugely negative ones exactly there -> the pieces keep far
+    # more than they have room for.  Both must end in the same lists (the second stage then
+    # selects on the whole row).
+    pos = sample_positions(N)
     huge = scores.clone()
     huge[:, :, pos.to(DEV)] = 1e30
     check_select(oracle, huge, N, min(N // 8, 3 * len(pos)), 0, 0)
     low = scores.clone()
     low[:, :, pos.to(DEV)] = -1e30
     check_select(oracle, low, N, ks[0], 0, 0)
+
+
+def sample_positions(N, lo=0, hi=None):
+    """Positions that the first stage of a selection by pieces may sample: four adjacent scores at
+    each of up to 1024 places spread evenly over the candidates (a workgroup of T threads looks at
+    the places t * span / T, T = 256, 512 or 1024: all on this grid)."""
+    hi = N if hi is None else hi
+    span = hi - lo
+    start = torch.tensor([(lo + (t * span) // 1024) & ~3 for t in range(1024)])
+    pos = (start[:, None] + torch.arange(4)[None, :]).reshape(-1)
+    return torch.unique(pos[pos < N])
+
+
+def test_select_pieces_many_rows(oracle):
+    """Enough long rows that the pieces take their widest form (512 threads, 16384 scores)."""
+    say("select by pieces, 128 rows")
+    N, k = 70001, 4096
+    stride = (N + 3) // 4 * 4
+    scores = randn((2, 64, stride), torch.float32, 77)
+    check_select(oracle, scores, N, k, 0, 0)
+    check_select(oracle, scores, N, 7000, 128, 256)
+    # every kept score in one wave's span: its LDS region overflows and the piece takes the slower path
+    asc = torch.arange(stride, dtype=torch.float32).view(1, 1, -1).expand(2, 64, stride).contiguous().to(DEV)
+    check_select(oracle, asc, N, k, 0, 0)
+    mixed = scores.clone()
+    mixed[:, ::2, 20000:23000] += 100.0  # a dense block of large scores in every other row
+    check_select(oracle, mixed, N, k, 3, 9)
+    pos = sample_positions(N)
+    low = scores.clone()
+    low[:, :, pos.to(DEV)] = -1e30
+    check_select(oracle, low, N, k, 0, 0)
+    nan = scores.clone()
+    nan[:, :, ::5] = float("nan")
+    nan[:, :, 1::5] = float("-inf")
+    check_select(oracle, nan, N, 60000, 0, 0)  # the threshold falls among the NaN / -inf ties
 
 
 @pytest.mark.parametrize("N", [777, 9000, 66000])
