@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kAttnThreads, kAttnWavesPerSimd) void attn_kernel(A
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
+  const int wave = wave_id();
   const int grp = lane / LPR;
   const int sub = lane % LPR;
   // Workgroups go to the 8 XCDs round-robin by their linear index, and every XCD has an L2 of
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_group_kernel(AttnArgs a) {
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
+  const int wave = wave_id();
   const int grp = lane / LPR;
   const int sub = lane % LPR;
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;

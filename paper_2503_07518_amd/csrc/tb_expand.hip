@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kExpThreads) void expand_cluster_kernel(ExpandArgs 
   __shared__ DebtMap s_map[kExpWaves];
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
+  const int wave = wave_id();
   const int64_t u = blockIdx.x;
   const int32_t* in = a.idx_in + u * a.cap_in;
   int32_t* out = a.idx_out + u * a.cap_out;

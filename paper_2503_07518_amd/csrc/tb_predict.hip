@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kPredThreads) void hidden_kernel(PredictArgs a) {
   extern __shared__ float s_x[];  // [BC][staged_len(E)]
   const int e_pad = staged_len<EPL>(a.E);
   __shared__ float s_red[kPredWaves][BC];
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = wave_id();
   const int b0 = blockIdx.y * BC;
   const int nb = min(BC, a.B - b0);
   const T* h = static_cast<const T*>(a.h);
@@ -332,7 +332,7 @@ __global__ __launch_bounds__(kPredThreads) void output_kernel(PredictArgs a) {
   constexpr int kStep = kWave * EPL;
   extern __shared__ float s_z[];  // [BC][staged_len(hidden)]
   const int h_pad = staged_len<EPL>(a.hidden);
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = wave_id();
   const int b0 = blockIdx.y * BC;
   const int nb = min(BC, a.B - b0);
   const int n_out = a.G * a.Hq * a.Dimp;
@@ -516,7 +516,7 @@ __device__ inline void mfma_walk(const bf16_t* wrow, const float* const (&xrow)[
 template <int MT>
 __global__ __launch_bounds__(kHidMfmaWaves * kWave) void hidden_mfma_kernel(PredictArgs a) {
   __shared__ float s_red[kHidMfmaWaves][MT][256];
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = wave_id();
   const int r = lane % 16, q = lane / 16;
   const int n0 = blockIdx.x * 16, b0 = blockIdx.y * (16 * MT);
   const bf16_t* wrow = static_cast<const bf16_t*>(a.W1) + static_cast<int64_t>(n0 + r) * a.E + q * 8;
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(kHidMfmaWaves * kWave) void hidden_mfma_kernel(Pred
 // bf16 and scattered to q_imp[slot][b][head][j].
 template <int MT>
 __global__ __launch_bounds__(kOutMfmaWaves * kWave) void output_mfma_kernel(PredictArgs a) {
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = wave_id();
   const int r = lane % 16, q = lane / 16;
   const int n_out = a.G * a.Hq * a.Dimp;
   const int n0 = (blockIdx.x * kOutMfmaWaves + wave) * 16, b0 = blockIdx.y * (16 * MT);

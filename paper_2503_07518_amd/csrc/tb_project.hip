@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kMfmaThreads) void project_mfma_kernel(ProjectArgs 
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
+  const int wave = wave_id();
   const int b = blockIdx.z, h = blockIdx.y;
   const int col = lane & 31, kh = lane >> 5;
 

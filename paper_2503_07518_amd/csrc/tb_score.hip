@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreArgs a) 
   static_assert(G <= 16, "one MFMA column per query head of the group");
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  const int wave = tid / kWave;
+  const int wave = wave_id();
   const int i16 = lane & 15, kb = lane >> 4;
   const int b = blockIdx.z;
   const int hkv = blockIdx.y;
