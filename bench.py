@@ -26,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X datasheet HBM3E bandwidth
+GRAPH_MIN_STEPS = 32     # steps that one HIP graph of the timed loop holds at least: the layers of the modelled network
 
 
 
@@ -303,28 +304,32 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / n_steps  # us per call
 
+    # calls per graph: one per buffer copy, repeated until the graph holds at least as many steps
+    # as the model has layers (a serving loop captures a whole forward pass: one step per layer)
+    per_graph = copies * max(1, -(-GRAPH_MIN_STEPS // copies))
+
     def time_graph(fn, n_steps, warmup):
-        """Replay a HIP graph that holds one call per buffer copy (what a serving loop that
-        captures a whole forward pass does).  Exactly n_steps calls are timed: whole replays of
-        that graph plus one replay of a shorter graph for the remainder."""
+        """Replay a HIP graph of `per_graph` calls that go round the buffer copies.  Exactly n_steps
+        calls are timed: whole replays of that graph plus one replay of a shorter graph for the
+        remainder."""
         def capture(n_calls):
             g = torch.cuda.CUDAGraph()
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(side):
                 with torch.cuda.graph(g, stream=side):
-                    for b in bufs[:n_calls]:
-                        fn(b)
+                    for i in range(n_calls):
+                        fn(bufs[i % copies])
             torch.cuda.current_stream().wait_stream(side)
             return g
 
-        reps, rest = divmod(n_steps, copies)
-        g_full = capture(copies) if reps or warmup >= copies else None
+        reps, rest = divmod(n_steps, per_graph)
+        g_full = capture(per_graph) if reps or warmup >= per_graph else None
         g_rest = capture(rest) if rest else None
-        for _ in range(warmup // copies):
+        for _ in range(warmup // per_graph):
             g_full.replay()
-        if warmup % copies:
-            capture(warmup % copies).replay()
+        if warmup % per_graph:
+            capture(warmup % per_graph).replay()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         cur = torch.cuda.current_stream()
@@ -358,10 +363,10 @@ def main():
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             with torch.cuda.graph(g, stream=side):
-                for b in bufs:
-                    step(b)
+                for i in range(per_graph):
+                    step(bufs[i % copies])
         torch.cuda.current_stream().wait_stream(side)
-        n_rep = max(20, min(200, args.steps // copies))
+        n_rep = max(20, min(200, args.steps // per_graph))
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_rep + 1)]
         g.replay()
         evs[0].record()
@@ -369,9 +374,9 @@ def main():
             g.replay()
             evs[i + 1].record()
         torch.cuda.synchronize()
-        per = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 / copies for i in range(n_rep))
+        per = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 / per_graph for i in range(n_rep))
         pct = {"p10": round(per[n_rep // 10], 3), "median": round(per[n_rep // 2], 3), "p90": round(per[(n_rep * 9) // 10], 3),
-               "replays": n_rep, "steps_per_replay": copies}
+               "replays": n_rep, "steps_per_replay": per_graph}
 
     timer = (lambda fn: time_graph(fn, args.steps, args.warmup)[0]) if use_graph else (
         lambda fn: time_eager(fn, args.steps, args.warmup))
@@ -474,6 +479,7 @@ def main():
             "d_imp": cfg.Dimp, "k": cfg.k, "sink": cfg.sink, "window": cfg.window,
             "buffer_copies": copies, "kv_layout": args.kv_layout,
             "kv_memory": "pinned host" if args.kv_host else "hbm", "launch": "hipgraph" if use_graph else "eager",
+            "steps_per_graph": per_graph if use_graph else None,
         },
         "step_hbm": {
             "algorithmic_bytes": bytes_step, "achieved": round(step_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
