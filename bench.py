@@ -16,6 +16,7 @@ Prints ONE JSON line; its main fields:
 from __future__ import annotations
 
 import argparse
+import types
 import json
 import os
 import sys
@@ -26,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X datasheet HBM3E bandwidth
+PRODUCER_GROUP = 4       # consumer layers per producer layer (Sec. 4, predictor architecture)
 GRAPH_MIN_STEPS = 32     # steps that one HIP graph of the timed loop holds at least: the layers of the modelled network
 
 
@@ -59,6 +61,7 @@ def parse_args():
                     help="offloaded cache: K and V in pinned host memory, projected keys on the GPU; "
                          "only the selected rows cross the host link")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-group", action="store_true", help="skip the producer-group (batched scoring and selection of 4 layers) timing")
     ap.add_argument("--no-headless", action="store_true",
                     help="skip the timings of the head-less variant (keeps a profile of the per-head kernels clean)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -452,6 +455,69 @@ def main():
         step(bufs[0])       # restore copy 0's per-head outputs, which the parity check reads
         torch.cuda.synchronize()
 
+    # Producer groups (Sec. 3.3, batching of the predictor operations): the importance queries of
+    # the G = 4 consumer layers of a producer are known together, so their scoring and selection
+    # run as one batched call each (the layers' projected-key caches stacked along the batch axis
+    # of one descriptor), followed by the layers' attention calls one after the other.
+    group = None
+    if use_graph and not args.kv_host and not args.no_group and copies >= 2 and cfg.B * PRODUCER_GROUP * probe.nbytes() < (24 << 30):
+        G4 = PRODUCER_GROUP
+        n_groups = max(2, -(-copies // G4))
+        layers = list(bufs)
+        while len(layers) < n_groups * G4:  # whole groups of distinct layers
+            layers.append(LayerBuffers(cfg, len(layers), tb, workloads, torch, args.kv_layout, False))
+        groups = []
+        for gi in range(n_groups):
+            ls = layers[gi * G4:(gi + 1) * G4]
+            gb = types.SimpleNamespace(layers=ls)
+            gb.Kimp = torch.cat([b.Kimp for b in ls], dim=0)  # [G*B][Hkv][N][d']
+            gb.q_imp = torch.cat([b.q_imp for b in ls], dim=0)
+            gb.desc = tb.make_desc(cfg.N, cfg.Hq, Kimp=gb.Kimp)
+            gb.scores = torch.empty((G4 * cfg.B, cfg.Hq, (cfg.N + 3) // 4 * 4), dtype=torch.float32, device="cuda")
+            gb.idx = torch.zeros((G4 * cfg.B, cfg.Hq, probe.need), dtype=torch.int32, device="cuda")
+            gb.cnt = torch.zeros((G4 * cfg.B, cfg.Hq), dtype=torch.int32, device="cuda")
+            gb.ws = tb.new_workspace(tb.TB_OP_SELECT, gb.desc, probe.need)
+            groups.append(gb)
+
+        def group_step(gb):
+            tb.tb_score(gb.desc, gb.q_imp, gb.Kimp, 1.0, gb.scores)
+            tb.tb_select_topk(gb.desc, gb.scores, cfg.k, cfg.sink, cfg.window, gb.idx, gb.cnt, gb.ws)
+            for li, b in enumerate(gb.layers):
+                tb.tb_sparse_decode_attn(b.desc, b.q, b.K, b.V, gb.idx[li * cfg.B:(li + 1) * cfg.B],
+                                         gb.cnt[li * cfg.B:(li + 1) * cfg.B], probe.need, cfg.sm_scale, b.out, b.lse, b.ws)
+
+        for gb in groups:
+            group_step(gb)
+        torch.cuda.synchronize()
+        # the batched calls select what the per-layer calls select (same kernels, same scores)
+        same = all(torch.equal(gb.idx[li * cfg.B:(li + 1) * cfg.B], b.idx) and torch.equal(gb.cnt[li * cfg.B:(li + 1) * cfg.B], b.cnt)
+                   for gb in groups for li, b in enumerate(gb.layers) if b in bufs)
+        gg = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        n_calls = n_groups * max(1, -(-GRAPH_MIN_STEPS // (n_groups * G4)))
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(gg, stream=side):
+                for i in range(n_calls):
+                    group_step(groups[i % n_groups])
+        torch.cuda.current_stream().wait_stream(side)
+        gg.replay()
+        torch.cuda.synchronize()
+        n_rep = max(3, args.steps // (n_calls * G4))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n_rep):
+            gg.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us_layer = e0.elapsed_time(e1) * 1e3 / (n_rep * n_calls * G4)
+        group = {"layers_per_group": G4, "us_per_layer": round(us_layer, 3), "groups_of_buffers": n_groups,
+                 "layer_steps_timed": n_rep * n_calls * G4, "lists_equal_per_layer_calls": bool(same),
+                 "note": "scoring and selection of a producer's 4 consumer layers as one batched call each, then 4 attention calls"}
+        step(bufs[0])       # restore copy 0's outputs, which the parity check reads
+        torch.cuda.synchronize()
+        del groups, layers
+
     elt = cfg.elt_bytes
     bytes_kimp = cfg.B * cfg.Hkv * cfg.N * cfg.Dimp * elt
     bytes_gather = selected_rows * 2 * cfg.D * elt
@@ -521,6 +587,7 @@ def main():
         # head-less selection (one list per batch element for all heads): scoring and selection
         # of one importance head, attention over the shared list
         "headless": None if us_hl_step is None else {"us_step": round(us_hl_step, 3), "attn_us": round(us_hl_attn, 3)},
+        "producer_group": group,
         "step_us_spread": pct,
         "device_copy_256MiB_GBps": round(copy_gbps, 1),
         # measured read ceiling of this machine, and the same kernels' rates against it

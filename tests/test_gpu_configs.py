@@ -229,3 +229,50 @@ def test_c4_interval_neighbors_full_size(oracle):
     full = {p + 1 + (p // cfg.P) % (cfg.P - 1) for p in range(0, cfg.steps, cfg.P)}
     n_full = interval_case(oracle, cfg, steps=cfg.steps, full_reuse_steps=full)
     assert n_full == cfg.steps // cfg.P
+
+
+def test_producer_group_batched_scoring_and_selection(oracle):
+    """Sec. 3.3 batches the predictor operations of a producer's consumer layers: the projected-key
+    caches of 4 layers stacked along the batch axis of one descriptor, one scoring and one
+    selection call for all of them, then one attention call per layer on its slice of the lists.
+    Same lists and outputs as per-layer calls, and the lists are the oracle's."""
+    say("producer group: 4 layers scored and selected in one call each (C2 shape, N = 32768)")
+    cfg = workloads.C2
+    G, B, Hq, N, D = 4, cfg.B, cfg.Hq, cfg.N, cfg.D
+    layers = []
+    for layer in range(G):
+        data = workloads.make_layer(cfg, layer=layer, device=DEV)
+        K, V = data["K"], data["V"]
+        Kimp = torch.zeros((B, cfg.Hkv, N, cfg.Dimp), dtype=K.dtype, device=DEV)
+        d = tb.make_desc(N, Hq, K=K, V=V, Kimp=Kimp)
+        tb.tb_project_keys(d, K, data["W"], Kimp, 0, N)
+        workloads.apply_kimp_row_scale(Kimp, data["kimp_row_scale"])
+        layers.append((d, K, V, Kimp, data["q"][0].contiguous(), data["q_imp"][0].contiguous()))
+    need = tb.policy_count(N, cfg.k, 0, 0)
+    stride = (N + 3) // 4 * 4
+    gKimp = torch.cat([l[3] for l in layers], dim=0)
+    gq_imp = torch.cat([l[5] for l in layers], dim=0)
+    gd = tb.make_desc(N, Hq, Kimp=gKimp)
+    gscores = torch.empty((G * B, Hq, stride), dtype=torch.float32, device=DEV)
+    gidx = torch.full((G * B, Hq, need), -7, dtype=torch.int32, device=DEV)
+    gcnt = torch.zeros((G * B, Hq), dtype=torch.int32, device=DEV)
+    tb.tb_score(gd, gq_imp, gKimp, 1.0, gscores)
+    tb.tb_select_topk(gd, gscores, cfg.k, 0, 0, gidx, gcnt, tb.new_workspace(tb.TB_OP_SELECT, gd, need))
+    torch.cuda.synchronize()
+    ridx, rcnt = oracle.select_topk(np_of(gscores)[:, :, :N], cfg.k, 0, 0)
+    assert np.array_equal(np_of(gcnt), rcnt) and np.array_equal(np_of(gidx)[:, :, :need], ridx[:, :, :need])
+    for li, (d, K, V, Kimp, q, q_imp) in enumerate(layers):
+        scores = torch.empty((B, Hq, stride), dtype=torch.float32, device=DEV)
+        idx = torch.full((B, Hq, need), -7, dtype=torch.int32, device=DEV)
+        cnt = torch.zeros((B, Hq), dtype=torch.int32, device=DEV)
+        out = torch.empty((B, Hq, D), dtype=torch.float32, device=DEV)
+        lse = torch.empty((B, Hq), dtype=torch.float32, device=DEV)
+        ws = tb.new_workspace(tb.TB_OP_DECODE_STEP, d, need)
+        tb.tb_decode_step(d, q_imp, Kimp, 1.0, q, K, V, cfg.k, 0, 0, cfg.sm_scale, scores, idx, cnt, out, lse, ws)
+        out2 = torch.empty_like(out)
+        lse2 = torch.empty_like(lse)
+        tb.tb_sparse_decode_attn(d, q, K, V, gidx[li * B:(li + 1) * B], gcnt[li * B:(li + 1) * B], need, cfg.sm_scale, out2, lse2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(scores, gscores[li * B:(li + 1) * B]), f"layer {li}: scores of the batched call differ"
+        assert torch.equal(idx, gidx[li * B:(li + 1) * B]) and torch.equal(cnt, gcnt[li * B:(li + 1) * B])
+        assert torch.equal(out, out2) and torch.equal(lse, lse2), f"layer {li}: attention on the batched lists differs"
