@@ -774,6 +774,7 @@ __device__ __forceinline__ uint32_t append_at_least(const float4 (&raw)[NT], con
   constexpr int kCap = R::kCap;
   constexpr int kPosOff = static_cast<int>(sizeof(rl.key) / 4);  // pos[i] is key[i + kPosOff]
   static_assert(offsetof(R, pos) == sizeof(rl.key), "pos follows key");
+  static_assert(offsetof(R, spill) == offsetof(R, pos) + sizeof(rl.pos), "the spill area follows pos");
   uint32_t* const lkey = rl.key + wave * kCap;
   uint32_t* const spare = rl.key + W * kCap + lane;
   uint32_t run = 0;
