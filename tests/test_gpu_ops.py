@@ -200,6 +200,16 @@ def sample_positions(N, lo=0, hi=None):
     return torch.unique(pos[pos < N])
 
 
+def test_select_pieces_row_count_not_a_multiple_of_eight(oracle):
+    """The first stage places the pieces of a row on one XCD and pads its launch to a multiple of
+    eight rows: 6 and 11 rows, sink and window, a ragged last piece."""
+    say("select by pieces, 6 and 11 rows")
+    for B, Hq, N in ((2, 3, 66003), (1, 11, 81925)):
+        scores = randn((B, Hq, (N + 3) // 4 * 4), torch.float32, 300 + Hq)
+        check_select(oracle, scores, N, 4096, 0, 0)
+        check_select(oracle, scores, N, 2000, 64, 100)
+
+
 def test_select_pieces_many_rows(oracle):
     """Enough long rows that the pieces take their widest form (512 threads, 16384 scores)."""
     say("select by pieces, 128 rows")
