@@ -81,8 +81,12 @@ tb_status tb_score(const tb_cache_desc* desc, const void* q_imp, const void* Kim
  * untouched.  count: int32 [B][Hq].  ws / ws_bytes are optional (NULL / 0 is fine): the selection
  * keeps its scratch on chip, except that long rows (N > 65536 with a budget of at most an
  * eighth of the candidates) are cut into pieces that are filtered by several compute units and
- * then combined, which needs tb_workspace_bytes(TB_OP_SELECT, desc, sink + k + window) bytes;
- * with less, one workgroup selects the whole row (same result, slower). */
+ * then combined, which needs tb_workspace_bytes(TB_OP_SELECT, desc, sink + k + window) bytes
+ * (8 bytes per slot for a kept score: at most min(2k + 4096, piece length) slots per piece of
+ * 16384 scores, so up to 8 N bytes per (b,h) -- 201 MB for B*Hq = 256, N = 131072, k = 4096);
+ * with less, one workgroup selects the whole row (same result, slower).  The batch axis may
+ * just as well run over the consumer layers of a producer (Sec. 3.3: their scoring and
+ * selection are batched): stack the layers' projected-key caches and queries along B. */
 tb_status tb_select_topk(const tb_cache_desc* desc, const float* scores, int64_t score_stride, int32_t k,
                          int32_t sink, int32_t window, int32_t* idx, int32_t* count, int64_t idx_cap, void* ws,
                          size_t ws_bytes, void* stream);
