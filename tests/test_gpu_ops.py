@@ -103,6 +103,9 @@ def test_project_strided_cache(oracle):
     (torch.float32, 1, 2, 2, 64, 300),
     (torch.bfloat16, 1, 4, 4, 64, 1),
     (torch.float32, 2, 8, 2, 32, 4097),
+    (torch.bfloat16, 1, 4, 4, 32, 257),    # the matrix-core form (bf16, 32 projected dims): one query head per KV head
+    (torch.bfloat16, 3, 6, 3, 32, 70),     # ... two, a ragged single workgroup
+    (torch.bfloat16, 1, 8, 1, 32, 9),      # ... eight, fewer rows than one matrix tile
 ])
 def test_score(oracle, dtype, B, Hq, Hkv, Dimp, N):
     say(f"score dtype={dtype} B={B} Hq={Hq} Hkv={Hkv} Dimp={Dimp} N={N}")
