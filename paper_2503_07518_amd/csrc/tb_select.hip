@@ -761,7 +761,6 @@ __device__ inline float score_of_key(uint32_t key) {
 }
 constexpr uint32_t kKeyOfMinusInf = 0x007FFFFFu;
 
-
 // Appends the candidates (positions in [lo, hi)) among the wave's NT tiles `raw` -- tile j holds
 // the positions pos0 + 256 j + 4 lane .. + 3 -- whose score is at least f_lo (`all`: every
 // candidate, NaN included) to the wave's region, and returns their number, the same in every
