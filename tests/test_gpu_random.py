@@ -57,6 +57,48 @@ def test_random_select(oracle, seed):
     assert np.array_equal(np.where(mask, np_of(idx)[..., :w], -1), np.where(mask, ridx, -1))
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_select_long_rows(oracle, seed):
+    """Rows beyond what one workgroup holds: the selection by pieces under random row counts,
+    budgets, sink / window ranges and score patterns (among them a dense block of large scores)."""
+    r = rng_of(5000 + seed)
+    N = int(pick(r, [65537, 65540, 70000, 81921, 100001, 131072, 131075, 200000, 262147]))
+    B, Hq = int(r.integers(1, 4)), int(pick(r, [1, 2, 5, 8, 13]))
+    k = int(pick(r, [1, 2, 100, 4096, N // 50, N // 9, N // 8, N // 7, N // 3]))
+    sink = int(pick(r, [0, 0, 1, 4, 128, 20000]))
+    window = int(pick(r, [0, 0, 1, 64, 256, 30000]))
+    kind = pick(r, ["normal", "normal", "few_values", "constant", "sorted", "specials", "cluster"])
+    print(f"[case] random long select seed={seed} N={N} B={B} Hq={Hq} k={k} sink={sink} window={window} kind={kind}", flush=True)
+    stride = (N + 3) // 4 * 4
+    g = torch.Generator().manual_seed(seed)
+    if kind == "normal":
+        s = torch.randn((B, Hq, stride), generator=g) * 10
+    elif kind == "few_values":
+        s = torch.randint(-3, 4, (B, Hq, stride), generator=g).float()
+    elif kind == "constant":
+        s = torch.full((B, Hq, stride), -2.5)
+    elif kind == "sorted":
+        s = torch.arange(stride, dtype=torch.float32).repeat(B, Hq, 1) * (1 if seed % 2 else -1)
+    elif kind == "cluster":
+        s = torch.randn((B, Hq, stride), generator=g)
+        a0 = int(r.integers(0, N - 5000))
+        s[:, :, a0:a0 + int(r.integers(500, 5000))] += 50
+    else:
+        s = torch.randn((B, Hq, stride), generator=g)
+        vals = torch.tensor([float("nan"), float("inf"), float("-inf"), -0.0, 0.0, 1e-45, -1e-45, 3.4e38])
+        s[torch.rand((B, Hq, stride), generator=g) < 0.3] = 0
+        sel = torch.rand((B, Hq, stride), generator=g) < 0.2
+        s[sel] = vals[torch.randint(0, len(vals), (int(sel.sum()),), generator=g)]
+    s = s.to(DEV)
+    idx, cnt = gpu_select(s, N, k, sink, window)
+    torch.cuda.synchronize()
+    ridx, rcnt = oracle.select_topk(np_of(s)[:, :, :N], k, sink, window)
+    assert np.array_equal(np_of(cnt), rcnt)
+    w = ridx.shape[-1]
+    mask = np.arange(w)[None, None, :] < rcnt[..., None]
+    assert np.array_equal(np.where(mask, np_of(idx)[..., :w], -1), np.where(mask, ridx, -1))
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_decode_step(oracle, seed):
     r = rng_of(2000 + seed)
