@@ -587,7 +587,9 @@ def main():
         # head-less selection (one list per batch element for all heads): scoring and selection
         # of one importance head, attention over the shared list
         "headless": None if us_hl_step is None else {"us_step": round(us_hl_step, 3), "attn_us": round(us_hl_attn, 3)},
-        "producer_group": group,
+        "producer_group": None if group is None else dict(
+            group, algorithmic_bytes_per_layer=bytes_step, achieved=round(bytes_step / group["us_per_layer"] / 1e3, 1),
+            unit="GB/s", frac=round(bytes_step / group["us_per_layer"] / 1e3 / HBM_PEAK_GBPS, 4)),
         "step_us_spread": pct,
         "device_copy_256MiB_GBps": round(copy_gbps, 1),
         # measured read ceiling of this machine, and the same kernels' rates against it
