@@ -121,7 +121,8 @@ struct Found {
   uint32_t total;           // sum of all bins
   uint32_t need_a, need_b;  // the targets that were searched
   uint32_t count_a;         // entries in bin_a (the histogram itself may be cleared for reuse once the walk is done)
-  uint32_t pad[3];
+  uint32_t count_b;         // entries in bin_b
+  uint32_t pad[2];
 };
 static_assert(sizeof(Found) == 48, "three 128-bit LDS reads");
 constexpr int kFoundWords = sizeof(Found) / 4;
@@ -189,6 +190,7 @@ __device__ inline Found find_bins(const uint32_t* s_hist, uint32_t extra, uint32
       } else {
         s_found->bin_b = bin;
         s_found->above_b = run;
+        s_found->count_b = cnt;
       }
     }
   }
@@ -208,7 +210,8 @@ __device__ inline Found find_bins(const uint32_t* s_hist, uint32_t extra, uint32
 // bracket holds.
 template <int W>
 __device__ inline void sample_bracket(const uint32_t* s_hist, uint32_t n_valid, uint32_t* s_extra, uint32_t* s_wsum,
-                                      Found* s_found, int kk, int64_t n_cand, uint32_t& b_lo, uint32_t& b_hi) {
+                                      Found* s_found, int kk, int64_t n_cand, uint32_t& b_lo, uint32_t& b_hi,
+                                      uint32_t* key_lo = nullptr) {
   const Found fb = find_bins<W>(s_hist, n_valid, s_extra, s_wsum, s_found, [&](uint32_t n_s, uint32_t& na, uint32_t& nb) {
     // (hardware reciprocal and square root: approximate, which is all a heuristic needs)
     const float frac = static_cast<float>(kk) * __builtin_amdgcn_rcpf(static_cast<float>(n_cand));
@@ -219,9 +222,24 @@ __device__ inline void sample_bracket(const uint32_t* s_hist, uint32_t n_valid, 
     nb = lo_f >= static_cast<float>(n_s) ? n_s + 1u : static_cast<uint32_t>(lo_f) + 1u;
   });
   b_hi = fb.need_a ? fb.bin_a : (kHistBins - 1);         // top bin of the bracket
-  b_lo = (fb.need_b <= fb.extra_total) ? fb.bin_b : 1u;  // bottom bin of the bracket
-  if (b_lo < 1u) b_lo = 1u;                              // bin 0 holds only "not a candidate"
+  const bool have_lo = fb.need_b <= fb.extra_total && fb.bin_b >= 1u;
+  b_lo = have_lo ? fb.bin_b : 1u;                        // bottom bin of the bracket (bin 0 holds only "not a candidate")
   if (b_hi < b_lo) b_hi = b_lo;
+  if (key_lo) {
+    // A key inside the bottom bin from which up a filter may keep: the bin is a sixteenth of an
+    // octave wide, and a distribution that is dense around the threshold puts several times the
+    // budget into it.  The sample's target rank is its j-th largest entry of count_b; with the
+    // bin's entries taken as evenly spread, everything from one spacing below that entry up is
+    // kept (a heuristic like the bracket itself: what decides is the exact count afterwards).
+    uint32_t lo_key = b_lo << kTopShift;
+    if (have_lo && fb.count_b > 0u) {
+      const uint32_t j = fb.need_b - fb.above_b;  // 1 .. count_b
+      const uint32_t width = 1u << kTopShift;
+      const uint32_t below = fb.count_b > j + 1u ? fb.count_b - (j + 1u) : 0u;  // spacings between the bin's lower edge and the cut
+      lo_key += static_cast<uint32_t>((static_cast<unsigned long long>(width) * below) / fb.count_b);
+    }
+    *key_lo = lo_key;
+  }
 }
 
 // Streamed rows (NT == 0) may keep the keys that fall inside the bracket in LDS, so that only
@@ -840,7 +858,7 @@ template <int W, int NT>
 struct PieceLds {
   uint32_t hist[kHistBins];
   __attribute__((aligned(16))) Found found;
-  uint32_t part[W], wsum[W], wgt[W];
+  uint32_t part[W], wsum[W];
   RegionLds<W, NT, kPieceCapPerTile> reg;
 };
 
@@ -892,9 +910,8 @@ __device__ __forceinline__ void piece_body(const SelectArgs& a, const int u, con
       }
     }
   }
-  uint32_t b_lo, b_hi;
-  sample_bracket<W>(pl.hist, n_valid, pl.part, pl.wsum, &pl.found, a.kk, span, b_lo, b_hi);
-  const uint32_t t_lo = b_lo << kTopShift;  // keys from here up are kept
+  uint32_t b_lo, b_hi, t_lo;  // t_lo: keys from here up are kept (inside the bracket's bottom bin)
+  sample_bracket<W>(pl.hist, n_valid, pl.part, pl.wsum, &pl.found, a.kk, span, b_lo, b_hi, &t_lo);
   // a score is kept when it is at least f_lo; a lower end at or below the key of -inf keeps
   // every candidate (NaN, whose key is that of -inf, included)
   const bool all = t_lo <= kKeyOfMinusInf;
@@ -928,46 +945,36 @@ __device__ __forceinline__ void piece_body(const SelectArgs& a, const int u, con
   }
 
   // A wave of this piece holds more kept scores than its region (a dense cluster of large
-  // scores): the same result from the registers, by prefix sums over the keys.
-  int lo_c = static_cast<int>(a.lo - base < 0 ? 0 : (a.lo - base > n_c ? n_c : a.lo - base));
-  int hi_c = static_cast<int>(a.hi - base < lo_c ? lo_c : (a.hi - base > n_c ? n_c : a.hi - base));
-  __syncthreads();  // every wave has read the counts
-  uint32_t run2 = 0;
+  // scores).  The counts of the pass above are right all the same, so every wave knows where
+  // its kept scores go: they are stored from the registers, positions from the compare masks.
+  uint32_t at = wave_base;  // kept scores of the waves and tiles before (the same in every lane)
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
-    uint32_t k4[4];
-    keys_of4(raw[j], lo_c, hi_c, wspan0 + j * kWaveTile + lane * 4, k4);
-    uint32_t cnt = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) cnt += k4[e] >= t_lo ? 1u : 0u;
-    run2 += __builtin_amdgcn_readlane(wave_incl_scan_u32(cnt), kWave - 1);
-  }
-  if (lane == 0) pl.wgt[wave] = run2;
-  __syncthreads();
-  uint32_t total2;
-  uint32_t at = wave_entries_scan<W>(pl.wgt, total2);  // kept keys of the waves and tiles before
-  if (tid < 3) hdr[tid] = tid == 0 ? total2 : (tid == 1 ? b_lo : b_hi);
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    uint32_t k4[4];
-    keys_of4(raw[j], lo_c, hi_c, wspan0 + j * kWaveTile + lane * 4, k4);
-    uint32_t cnt = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) cnt += k4[e] >= t_lo ? 1u : 0u;
-    const uint32_t incl = wave_incl_scan_u32(cnt);
-    uint32_t pos = at + incl - cnt;
+    const int n_t = pos0 + j * kWaveTile;
+    if (n_t >= a.hi || n_t + kWaveTile <= a.lo) continue;
+    const int p0 = n_t + lane * 4;
+    const float v[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
+    bool t[4];
+    unsigned long long m[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      if (k4[e] >= t_lo) {
-        if (pos < static_cast<uint32_t>(a.cap)) {
-          out_idx[pos] = static_cast<int32_t>(base) + wspan0 + j * kWaveTile + lane * 4 + e;
-          out_key[pos] = k4[e];
+      t[e] = (all || v[e] >= f_lo) && p0 + e >= a.lo && p0 + e < a.hi;  // (the test of the pass above)
+      m[e] = __ballot(t[e]);
+    }
+    uint32_t o = mbcnt64(m[3], mbcnt64(m[2], mbcnt64(m[1], mbcnt64(m[0], at))));
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (t[e]) {
+        if (o < static_cast<uint32_t>(a.cap)) {
+          out_idx[o] = p0 + e;
+          out_key[o] = score_key(v[e]);
         }
-        ++pos;
+        ++o;
       }
     }
-    at += __builtin_amdgcn_readlane(incl, kWave - 1);
+    at += popc64(m[0]) + popc64(m[1]) + popc64(m[2]) + popc64(m[3]);
   }
+  if (tid < 3) hdr[tid] = tid == 0 ? total : (tid == 1 ? b_lo : b_hi);
 }
 
 // ---- stage B.  One workgroup per row: builds the table of the pieces' kept keys and selects
@@ -1018,7 +1025,9 @@ __global__ __launch_bounds__(W * kWave) void prefilter_kernel(SelectArgs a) {
   const int64_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int64_t u = (slot / a.pieces) * 8 + xcd;
   if (u >= a.units) return;  // (the launch is padded to a multiple of eight rows)
-  piece_body<W, NT>(a, static_cast<int>(u), static_cast<int>(slot % a.pieces), sl);
+  // the pieces of a row from its end backwards: with scores that favour recent positions the
+  // last pieces keep the most and take the longest, so they should not be the last to start
+  piece_body<W, NT>(a, static_cast<int>(u), a.pieces - 1 - static_cast<int>(slot % a.pieces), sl);
 }
 
 template <int W>

@@ -231,6 +231,14 @@ def test_select_pieces_many_rows(oracle):
     low = scores.clone()
     low[:, :, pos.to(DEV)] = -1e30
     check_select(oracle, low, N, k, 0, 0)
+    # flat distributions put several budgets' worth of scores into one coarse bin around the
+    # threshold (the kept scores are cut inside that bin), a ramp towards recent positions puts
+    # nearly all kept scores into the last piece (its waves' LDS regions overflow)
+    g = torch.Generator().manual_seed(5)
+    flat = (1.0 + torch.rand((2, 64, stride), generator=g)).to(DEV)
+    check_select(oracle, flat, N, k, 0, 0)
+    ramp = (torch.arange(stride, dtype=torch.float32).view(1, 1, -1) * (8.0 / N) + torch.randn((2, 64, stride), generator=g)).to(DEV)
+    check_select(oracle, ramp, N, k, 16, 32)
     nan = scores.clone()
     nan[:, :, ::5] = float("nan")
     nan[:, :, 1::5] = float("-inf")
